@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the extend-attention hot path on one MI355X.
+
+One "step" = cp_write_kv (append the new K/V to the paged cache) followed by
+cp_extend_attention (suffix rows attend to cached prefix + own keys) over one batch of seeded
+synthetic input that is already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-extra] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def _workload(name: str):
+    import workloads as W
+    table = {
+        "tiny_extend": W.config1_tiny,
+        "rag_fixed": W.config2_rag_fixed,
+        "rag_zipf": W.config3_rag_zipf,
+        "long_context_32k": W.config4_long_context,
+        "ctx128k_zero_reuse": lambda: W.config5_128k(False),
+        "ctx128k_reuse": lambda: W.config5_128k(True),
+        "short_extend_probe": W.probe_short_extend,
+    }
+    return table[name]()
+
+
+def algorithmic_bytes(w) -> float:
+    """Bytes that must move once: q in, out, new K/V read twice (attention, cache write) and
+    written once, every distinct prefix page once per request."""
+    T, Hq, Hkv, D = w.total_extend, w.num_q_heads, w.num_kv_heads, w.head_dim
+    q_out = 2.0 * T * Hq * D * 2
+    new_kv = 3.0 * T * Hkv * D * 2 * 2
+    prefix = float(w.prefix_lens.astype(np.int64).sum()) * Hkv * D * 2 * 2
+    return q_out + new_kv + prefix
+
+
+class Runner:
+    def __init__(self, w):
+        import torch
+        import paper_2511_03475_amd as cp
+        self.torch, self.cp, self.w = torch, cp, w
+        dev = "cuda:0"
+
+        def up(a):
+            a = np.ascontiguousarray(a)
+            if a.dtype == np.uint16:
+                a = a.view(np.int16)
+            return torch.from_numpy(a).to(dev)
+
+        self.q, self.k, self.v, self.pool = up(w.q), up(w.k_new), up(w.v_new), up(w.kv_pages)
+        self.table, self.pl, self.el = up(w.block_table), up(w.prefix_lens), up(w.extend_lens)
+        self.out = torch.empty_like(self.q)
+        self.shape = cp.Shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.page_size,
+                              w.num_pages, w.max_pages_per_req, w.prefix_lens, w.extend_lens,
+                              w.softmax_scale)
+        self.ws_bytes = cp.cp_workspace_bytes(self.shape)
+        self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=dev)
+        self.splits = cp.cp_num_splits(self.shape)
+
+    def step(self, stream, ev=None):
+        cp = self.cp
+        cp.cp_write_kv(self.k, self.v, self.pool, self.table, self.pl, self.el, stream, self.shape)
+        if ev is not None:
+            ev[0].record(stream)
+        cp.cp_extend_attention(self.q, self.k, self.v, self.pool, self.table, self.pl, self.el,
+                               self.out, stream, self.shape, self.ws, self.ws_bytes)
+        if ev is not None:
+            ev[1].record(stream)
+
+    def run(self, steps: int, warmup: int):
+        torch = self.torch
+        stream = torch.cuda.current_stream()
+        for _ in range(warmup):
+            self.step(stream)
+        events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                  for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step(stream, events[i])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        attn_ms = [a.elapsed_time(b) for a, b in events]
+        return (t1 - t0) * 1e3 / steps, float(np.mean(attn_ms)), float(np.min(attn_ms))
+
+
+def measure(name: str, steps: int, warmup: int):
+    t = time.perf_counter()
+    w = _workload(name)
+    gen_s = time.perf_counter() - t
+    r = Runner(w)
+    ms_step, attn_ms, attn_min = r.run(steps, warmup)
+    flops = w.flops()
+    res = {
+        "workload": name, "batch": w.batch, "q_heads": w.num_q_heads, "kv_heads": w.num_kv_heads,
+        "prefix_tokens": int(w.prefix_lens.astype(np.int64).sum()), "extend_tokens": w.total_extend,
+        "flops": flops, "splits": r.splits, "steps": steps,
+        "ms_per_step": ms_step, "attn_ms_avg": attn_ms, "attn_ms_min": attn_min,
+        "tflops_step": flops / (ms_step * 1e-3) / 1e12,
+        "tflops_attn": flops / (attn_ms * 1e-3) / 1e12,
+        "frac_mfma_peak": flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "alg_bytes": algorithmic_bytes(w),
+        "gbs_step": algorithmic_bytes(w) / (ms_step * 1e-3) / 1e9,
+        "gen_s": gen_s,
+    }
+    if w.notes:
+        res["notes"] = {k: v for k, v in w.notes.items()}
+    return w, r, res
+
+
+def cpu_baseline(w, budget_s: float = 15.0):
+    """The fp64 oracle, as it stands, timed on a seeded row sample of the same workload."""
+    import oracle
+    rng = np.random.default_rng(12345)
+    T = w.total_extend
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    cu = w.cu_extend
+
+    def pairs_of(rows):
+        rr = np.searchsorted(cu, rows, side="right") - 1
+        return int((w.prefix_lens[rr].astype(np.int64) + (rows - cu[rr]) + 1).sum())
+
+    probe = np.sort(rng.choice(T, size=min(T, max(threads // 4, 2)), replace=False)).astype(np.int32)
+    t = time.perf_counter()
+    oracle.attention_of(w, rows=probe)
+    dt = time.perf_counter() - t
+    per_pair = dt / max(pairs_of(probe), 1)
+    mean_pairs = w.pairs_per_head() / max(T, 1)
+    n = int(max(min(budget_s / max(per_pair * mean_pairs, 1e-9), T), 1))
+    rows = np.sort(rng.choice(T, size=n, replace=False)).astype(np.int32)
+    t = time.perf_counter()
+    oracle.attention_of(w, rows=rows)
+    dt = time.perf_counter() - t
+    fl = 4.0 * w.head_dim * w.num_q_heads * pairs_of(rows)
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n} of {T} extend rows (seeded, all {w.num_q_heads} q heads), "
+                      f"{dt:.1f} s of fp64 oracle; full workload extrapolates to "
+                      f"{w.flops() / (fl / dt):.0f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="long_context_32k")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only; use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2511_03475_amd as cp
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    cp.load_library()   # raises if the HIP library has not been built
+
+    w, r, head = measure(args.workload, args.steps, args.warmup)
+    cpu = None if args.no_cpu else cpu_baseline(w)
+    del r
+    torch.cuda.empty_cache()
+
+    extra = []
+    if not args.no_extra:
+        for name in ("tiny_extend", "rag_fixed", "rag_zipf", "long_context_32k",
+                     "ctx128k_zero_reuse", "ctx128k_reuse", "short_extend_probe"):
+            if name == args.workload:
+                extra.append({k: head[k] for k in head})
+                continue
+            steps = 5 if name.startswith("ctx128k") or name == "rag_zipf" else 20
+            _, rr, res = measure(name, steps, 2)
+            extra.append(res)
+            del rr
+            torch.cuda.empty_cache()
+    by = {e["workload"]: e for e in extra}
+    reuse = None
+    if "ctx128k_zero_reuse" in by and "ctx128k_reuse" in by:
+        reuse = {"measured_step": by["ctx128k_zero_reuse"]["ms_per_step"] / by["ctx128k_reuse"]["ms_per_step"],
+                 "measured_attn": by["ctx128k_zero_reuse"]["attn_ms_avg"] / by["ctx128k_reuse"]["attn_ms_avg"],
+                 "algorithmic_flop_ratio": by["ctx128k_zero_reuse"]["flops"] / by["ctx128k_reuse"]["flops"],
+                 "token_ratio": 8.0}
+
+    line = {
+        "metric": "extend-attention TFLOP/s and % of bf16 MFMA peak at 32k/128k ctx",
+        "value": head["tflops_step"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": head["batch"], "q_heads": head["q_heads"],
+                   "kv_heads": head["kv_heads"], "head_dim": 128, "page_size": 16,
+                   "prefix_tokens": head["prefix_tokens"], "extend_tokens": head["extend_tokens"],
+                   "step": "cp_write_kv + cp_extend_attention", "splits": head["splits"]},
+        "roofline": {"bound": "mfma", "kernel": "extend_attn_kernel",
+                     "achieved": head["tflops_attn"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": head["frac_mfma_peak"], "traffic": None,
+                     "avg_kernel_ms": head["attn_ms_avg"]},
+        "cpu_baseline": cpu,
+    }
+    if extra:
+        line["workloads"] = [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in e.items()
+                              if k not in ("notes",)} for e in extra]
+        zipf = by.get("rag_zipf", {}).get("notes")
+        if zipf:
+            line["rag_zipf_hit_ratio"] = zipf.get("token_hit_ratio")
+    if reuse:
+        line["reuse_speedup_128k"] = reuse
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,119 @@
+/*
+ * cp_extend: prefix-cached "extend" prefill attention over a paged KV cache (C ABI).
+ *
+ * Setting (paper, Section 1 and Section 2.1): during prefill an inference engine computes
+ * the K/V of a prompt; a prefix cache keeps the K/V of earlier prompts as blocks addressed by
+ * block identifiers; a request whose prompt starts with a cached prefix computes only its
+ * uncached suffix, reading the prefix K/V back from the cache, and stores the new K/V so that
+ * later requests can reuse it.  Exact-prefix reuse does not change the result (Section 1), so
+ * the operations below are plain causal scaled-dot-product attention and a cache append.
+ *
+ * Notation: B requests; request r has P_r cached prefix tokens and E_r extend (suffix) tokens;
+ * T = sum_r E_r; cu[r] = E_0 + ... + E_{r-1}; Hq query heads, Hkv KV heads, G = Hq / Hkv;
+ * D = head_dim; PS = page_size.
+ *
+ * Memory layouts (all dense; bf16 carried as raw 16-bit patterns):
+ *   q, out         [T][Hq][D]    bf16   DEVICE   request r owns rows [cu[r], cu[r] + E_r)
+ *   k_new, v_new   [T][Hkv][D]   bf16   DEVICE
+ *   kv_pages       [num_pages][2][Hkv][PS][D] bf16 DEVICE  (index 0 = K, 1 = V); one
+ *                  (page, K|V, head) slab is PS*D*2 contiguous bytes
+ *   block_table    [B][max_pages_per_req] int32 DEVICE; entry i is the physical page that
+ *                  holds tokens [i*PS, (i+1)*PS) of the request; entries at or beyond
+ *                  ceil((P_r + E_r) / PS) are never read
+ *   prefix_lens, extend_lens [B] int32 DEVICE, with identical HOST copies in cp_shape
+ *
+ * Ownership: the caller owns every buffer and the stream.  The library allocates no device
+ * memory, never synchronises and never changes the current device; all work is enqueued on
+ * `stream` (a hipStream_t passed as void*; NULL is the default stream).  All pointers must be
+ * 16-byte aligned.
+ *
+ * Errors: every entry point validates its host-visible arguments before any launch and
+ * returns CP_OK or a negative code; nothing is enqueued when a code other than CP_OK or
+ * CP_ERR_LAUNCH is returned.  Device-side contents (block_table entries inside
+ * [0, num_pages), device lengths equal to the host copies) are not validated.
+ */
+#ifndef CP_EXTEND_H
+#define CP_EXTEND_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    CP_OK = 0,
+    CP_ERR_NULL = -1,      /* a required pointer is NULL */
+    CP_ERR_SHAPE = -2,     /* unsupported or inconsistent shape (see cp_shape) */
+    CP_ERR_WORKSPACE = -3, /* workspace missing, too small or misaligned */
+    CP_ERR_LAUNCH = -4     /* the HIP runtime reported a launch error */
+};
+
+typedef struct cp_shape {
+    int32_t batch;             /* B >= 1 */
+    int32_t num_q_heads;       /* Hq >= 1 */
+    int32_t num_kv_heads;      /* Hkv >= 1, Hq % Hkv == 0; q head h uses KV head h / (Hq/Hkv) */
+    int32_t head_dim;          /* must be 128 */
+    int32_t page_size;         /* must be 16 */
+    int32_t num_pages;         /* pages in kv_pages, >= 1 */
+    int32_t max_pages_per_req; /* row stride of block_table; >= ceil((P_r+E_r)/PS) for all r */
+    int32_t total_extend;      /* T; must equal the sum of h_extend_lens */
+    float softmax_scale;       /* multiplies q.k before the softmax; finite and > 0 */
+    int32_t num_splits;        /* split-K factor over the keys: 0 = chosen by the library,
+                                  1 = never split, 2..64 = forced */
+    const int32_t *h_prefix_lens; /* HOST, length B, each >= 0 */
+    const int32_t *h_extend_lens; /* HOST, length B, each >= 0 */
+} cp_shape;
+
+/*
+ * Bytes of device scratch that cp_extend_attention needs for this shape (0 when the keys
+ * are not split).  A pure function of *shape, including the host length arrays.  Returns 0
+ * for an invalid shape (cp_extend_attention then reports the error).
+ */
+size_t cp_workspace_bytes(const cp_shape *shape);
+
+/* The split-K factor cp_extend_attention will use for this shape (>= 1; 0 if invalid). */
+int32_t cp_num_splits(const cp_shape *shape);
+
+/*
+ * Extend attention (paper, Section 1: prefill over a prefix cache).  For request r, q head h,
+ * g = h / G and extend row i in [0, E_r):
+ *     key(j), val(j):  j <  P_r -> row j % PS of head g in page block_table[r][j / PS]
+ *                      j >= P_r -> row cu[r] + j - P_r of k_new / v_new, head g
+ *     s_j = softmax_scale * <q[cu[r]+i, h, :], key(j)>       for j = 0 .. P_r + i
+ *     out[cu[r]+i, h, :] = sum_j softmax(s)_j * val(j)
+ * Products are bf16 x bf16 accumulated in fp32, the softmax is fp32, out is rounded to bf16
+ * (nearest even).  The suffix K/V is read from k_new / v_new, never from kv_pages, so the
+ * result does not depend on whether cp_write_kv ran before, after or not at all.  kv_pages is
+ * only read.  Results are bitwise reproducible for a fixed shape (no atomics).
+ *
+ * workspace: DEVICE scratch of at least cp_workspace_bytes(shape) bytes, 256-byte aligned;
+ * may be NULL when that size is 0.  Its contents are undefined afterwards.
+ * Requests with E_r = 0 produce no rows.  Asynchronous on `stream`.
+ */
+int cp_extend_attention(const void *q, const void *k_new, const void *v_new,
+                        const void *kv_pages, const int32_t *block_table,
+                        const int32_t *prefix_lens, const int32_t *extend_lens, void *out,
+                        void *stream, const cp_shape *shape, void *workspace,
+                        size_t workspace_bytes);
+
+/*
+ * Cache append (paper, Section 1: the prefix cache stores the K/V of prior prompts).  For
+ * request r, row j < E_r and KV head g, the bit patterns of k_new[cu[r]+j, g, :] and
+ * v_new[cu[r]+j, g, :] are copied to page block_table[r][(P_r+j) / PS], slot (P_r+j) % PS.
+ * No other element of kv_pages is touched.  Two rows that map to the same destination slot
+ * (overlapping page lists of different requests) give an undefined winner.
+ * Asynchronous on `stream`.
+ */
+int cp_write_kv(const void *k_new, const void *v_new, void *kv_pages,
+                const int32_t *block_table, const int32_t *prefix_lens,
+                const int32_t *extend_lens, void *stream, const cp_shape *shape);
+
+/* Static, human-readable text for a status code. */
+const char *cp_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CP_EXTEND_H */

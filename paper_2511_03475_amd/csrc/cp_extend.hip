@@ -1,0 +1,617 @@
+// cp_extend: prefix-cached "extend" prefill attention over a paged KV cache for gfx950.
+//
+// Three kernels behind the C ABI of cp_extend.h:
+//   write_kv_kernel       cache append (paper, Section 1: the prefix cache stores prior K/V)
+//   extend_attn_kernel    suffix rows attend to cached prefix pages + their own K/V
+//                         (paper, Section 1 / Section 2.1: prefill over a prefix cache)
+//   merge_splits_kernel   combines split-K partial results
+//
+// Attention kernel layout.  One workgroup = 4 wavefronts = 128 query rows of one q head; each
+// wavefront owns 32 rows.  Keys are streamed in tiles of 64 through LDS.  Scores are computed
+// transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16 so that the accumulator lane
+// (lane % 32) is a query row: the softmax row reductions are then in-lane plus one exchange
+// between the two half-waves, the bf16 probabilities already sit in the B-operand layout of the
+// second product O^T = V^T P^T, and the per-row rescale of O is a per-lane scalar multiply.
+// V^T fragments come from LDS through the transposing read ds_read_b64_tr_b16.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cp_extend.h"
+
+namespace {
+
+constexpr int kD = 128;       // head dim
+constexpr int kPS = 16;       // tokens per page
+constexpr int kBM = 128;      // query rows per workgroup
+constexpr int kBN = 64;       // keys per tile
+constexpr int kThreads = 256; // 4 wavefronts
+constexpr int kXcds = 8;      // accelerator complex dies; workgroup ids round-robin over them
+constexpr int kMaxSplits = 64;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+struct AttnParams {
+    const uint16_t *q;
+    const uint16_t *k_new;
+    const uint16_t *v_new;
+    const uint16_t *kv_pages;
+    const int32_t *block_table;
+    const int32_t *prefix_lens;
+    const int32_t *extend_lens;
+    uint16_t *out;
+    float *part_o;  // [nsplit][T][Hq][D]   unnormalised partial outputs
+    float *part_ml; // [nsplit][T][Hq][2]   running max (log2 domain) and sum
+    int32_t batch, Hq, Hkv, G, max_pages, T;
+    int32_t nsplit;
+    int32_t items_per_head; // q tiles * G * nsplit
+    int32_t total_items;    // items_per_head * Hkv
+    int32_t items_per_xcd;  // ceil(total_items / 8)
+    float scale_log2;       // softmax_scale * log2(e)
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Maximum across the two half-waves (lane l and lane l ^ 32 end with the same value).
+__device__ __forceinline__ float halfwave_max(float x)
+{
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float halfwave_sum(float x)
+{
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// K/V tile of 64 keys, staged in registers between the global load and the LDS store.
+struct TileRegs {
+    u32x4 k[4];
+    u32x4 v[4];
+};
+
+template <bool kSplit>
+__global__ __launch_bounds__(kThreads, 2) void extend_attn_kernel(const AttnParams p)
+{
+    // 16-byte chunk c of key row r lives at chunk c ^ (r & 15) for K and c ^ ((r & 7) << 1)
+    // for V, which keeps both the row-per-lane K reads and the 8-row transposing V reads
+    // spread over all banks.
+    __shared__ __attribute__((aligned(16))) u32x4 lds_k[kBN * 16];
+    __shared__ __attribute__((aligned(16))) u32x4 lds_v[kBN * 16];
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const int lane = tid & 63;
+    const int j = lane & 31; // query row within the wave; also key row / d row of A operands
+    const int h = lane >> 5; // half-wave
+
+    // ---- which work item: consecutive workgroup ids land on different XCDs, so give each
+    // XCD a contiguous range of the item list (one KV head per XCD when Hkv == 8) and keep the
+    // items that stream the same K/V next to each other in time.
+    const int bid = blockIdx.x;
+    const int vid = (bid % kXcds) * p.items_per_xcd + bid / kXcds;
+    if (vid >= p.total_items) return;
+    const int kvh = vid / p.items_per_head;
+    int rem = vid - kvh * p.items_per_head;
+    const int split = rem % p.nsplit;
+    rem /= p.nsplit;
+    const int g = rem % p.G;
+    int qt_rank = rem / p.G;
+    const int head = kvh * p.G + g;
+
+    // requests in order; within a request the last (longest) q tile first
+    int r = 0, cu = 0, E = 0, t = 0;
+    for (; r < p.batch; ++r) {
+        E = p.extend_lens[r];
+        const int nt = (E + kBM - 1) / kBM;
+        if (qt_rank < nt) {
+            t = nt - 1 - qt_rank;
+            break;
+        }
+        qt_rank -= nt;
+        cu += E;
+    }
+    if (r >= p.batch) return;
+    const int P = p.prefix_lens[r];
+
+    const int q0 = t * kBM;                       // first extend row of the workgroup
+    const int row_i = q0 + wave * 32 + j;         // this lane's extend row (may be >= E)
+    const int rows_end = min(E, q0 + kBM);        // one past the last valid row of the tile
+    const int np_tiles = (P + kBN - 1) / kBN;     // prefix key tiles
+    const int ns_tiles = (rows_end + kBN - 1) / kBN; // suffix key tiles up to the diagonal
+    const int n_tiles = np_tiles + ns_tiles;
+    const int per_split = (n_tiles + p.nsplit - 1) / p.nsplit;
+    const int kt_begin = split * per_split;
+    const int kt_end = min(n_tiles, kt_begin + per_split);
+
+    const int64_t out_row = (int64_t)(cu + min(row_i, E - 1));
+    const bool row_valid = row_i < E;
+
+    if (kt_begin >= kt_end) {
+        // empty split: the merge skips entries whose sum is zero
+        if (kSplit && row_valid && h == 0) {
+            float *ml = p.part_ml + (((int64_t)split * p.T + out_row) * p.Hq + head) * 2;
+            ml[0] = -INFINITY;
+            ml[1] = 0.f;
+        }
+        return;
+    }
+
+    // ---- Q fragments, B operand of S^T = K Q^T: lane (j, h) holds q[row j][16 kk + 8 h ..+8)
+    bf16x8 qf[8];
+    {
+        const uint16_t *qp = p.q + (out_row * p.Hq + head) * kD + 8 * h;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+            qf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qp + 16 * kk));
+    }
+
+    // ---- addressing of this thread's share of a K/V tile: rows ld_row + 16 i, chunk ld_chunk
+    const int ld_row = tid >> 4;
+    const int ld_chunk = tid & 15;
+    const int32_t *table = p.block_table + (int64_t)r * p.max_pages;
+    const int64_t v_plane = (int64_t)p.Hkv * kPS * kD; // K slab -> V slab inside a page
+
+    auto load_tile = [&](int kt, TileRegs &tr) {
+        const uint16_t *ks[4];
+        const uint16_t *vs[4];
+        if (kt < np_tiles) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int tok = min(kt * kBN + i * 16 + ld_row, P - 1);
+                const int64_t page = table[tok >> 4];
+                ks[i] = p.kv_pages +
+                    (((page * 2 * p.Hkv + kvh) * kPS + (tok & 15)) * kD + ld_chunk * 8);
+                vs[i] = ks[i] + v_plane;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int srow = min((kt - np_tiles) * kBN + i * 16 + ld_row, E - 1);
+                const int64_t off = ((int64_t)(cu + srow) * p.Hkv + kvh) * kD + ld_chunk * 8;
+                ks[i] = p.k_new + off;
+                vs[i] = p.v_new + off;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            tr.k[i] = *(const __attribute__((address_space(1))) u32x4 *)(ks[i]);
+            tr.v[i] = *(const __attribute__((address_space(1))) u32x4 *)(vs[i]);
+        }
+    };
+    auto store_tile = [&](const TileRegs &tr) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = i * 16 + ld_row;
+            lds_k[row * 16 + (ld_chunk ^ (row & 15))] = tr.k[i];
+            lds_v[row * 16 + (ld_chunk ^ ((row & 7) << 1))] = tr.v[i];
+        }
+    };
+
+    // ---- per-lane LDS read offsets
+    // K, A operand of S^T: lane (j, h) reads 16 bytes of key row kb*32 + j at chunk 2 kk + h.
+    const int k_row_off = j * 16;   // in uint4 units, plus kb * 32 * 16
+    const int k_swz = j & 15;
+    // V^T, A operand of O^T = V^T P^T, through the transposing read: within a group of 16
+    // lanes, lane i supplies the address of 4 consecutive d of key row k0 + i / 4 and receives
+    // V[k0 .. k0+3][d0 + i].
+    const char *lds_v_bytes = reinterpret_cast<const char *>(lds_v);
+    int v_off[4]; // byte offset for d block db, before adding the key-row base
+    {
+        const int vr = 4 * h + ((lane & 15) >> 2);  // key row modulo 8
+        const int swz = vr << 1;
+        const int c_lane = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+            v_off[db] = vr * 256 + (((db * 4 + c_lane) ^ swz) << 4) + 8 * (lane & 1);
+    }
+
+    f32x16 o[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
+    float m_run = -INFINITY; // running row maximum, log2 domain (same in both half-waves)
+    float l_run = 0.f;       // running sum over this half-wave's keys only
+
+    TileRegs tr;
+    load_tile(kt_begin, tr);
+    store_tile(tr);
+    __syncthreads();
+
+    const float c = p.scale_log2;
+    const int wave_row0 = q0 + wave * 32;
+
+    for (int kt = kt_begin; kt < kt_end; ++kt) {
+        const bool has_next = kt + 1 < kt_end;
+        if (has_next) load_tile(kt + 1, tr);
+
+        const bool suffix = kt >= np_tiles;
+        const int key0 = suffix ? (kt - np_tiles) * kBN : kt * kBN; // first key of the tile
+        // suffix tile entirely above this wave's rows: nothing visible
+        const bool skip = suffix && key0 > wave_row0 + 31;
+        if (!skip) {
+            // ---- S^T = K Q^T : two 32-key blocks x 32 query rows
+            f32x16 s[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
+#pragma unroll
+                for (int kk = 0; kk < 8; ++kk) {
+                    const u32x4 kraw = lds_k[kb * 32 * 16 + k_row_off + ((2 * kk + h) ^ k_swz)];
+                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8, kraw), qf[kk], s[kb], 0, 0, 0);
+                }
+            }
+            // ---- mask keys that are not visible (boundary tiles only)
+            // accumulator element v of block kb is key kb*32 + 8*(v/4) + 4*h + v%4
+            const int vis = suffix ? (row_i - key0 + 1) : (P - key0); // visible keys in tile
+            const bool need_mask = suffix ? (key0 + kBN - 1 > wave_row0) : (key0 + kBN > P);
+            if (need_mask) {
+                const int vis_h = vis - 4 * h;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        if (kb * 32 + 8 * (v >> 2) + (v & 3) >= vis_h) s[kb][v] = -INFINITY;
+                    }
+            }
+            // ---- online softmax, one query row per lane
+            float mx = s[0][0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[0][v]);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[1][v]);
+            mx = halfwave_max(mx);
+            const float m_new = fmaxf(m_run, mx * c);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+                const float alpha = fast_exp2(m_run - m_use);
+                l_run *= alpha;
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+                m_run = m_new;
+            }
+            float psum = 0.f;
+            bf16x8 pb[2][2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int mm = 0; mm < 2; ++mm)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float pv = fast_exp2(fmaf(s[kb][8 * mm + e], c, -m_use));
+                        psum += pv;
+                        pb[kb][mm][e] = (__bf16)pv;
+                    }
+            l_run += psum;
+            // ---- O^T += V^T P^T : 4 d blocks x 4 steps of 16 keys
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int mm = 0; mm < 2; ++mm) {
+                    const int krow_bytes = (kb * 32 + mm * 16) * 256;
+#pragma unroll
+                    for (int db = 0; db < 4; ++db) {
+                        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (__attribute__((address_space(3))) s16x4 *)(lds_v_bytes + v_off[db] + krow_bytes));
+                        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (__attribute__((address_space(3))) s16x4 *)(lds_v_bytes + v_off[db] + krow_bytes + 8 * 256));
+                        const s16x8 vv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, vv), pb[kb][mm], o[db], 0, 0, 0);
+                    }
+                }
+        }
+        __syncthreads();
+        if (has_next) store_tile(tr);
+        __syncthreads();
+    }
+
+    // ---- epilogue.  o[db][v] is O^T[d = db*32 + 8*(v/4) + 4*h + v%4][row j]
+    const float l_tot = halfwave_sum(l_run);
+    if (!row_valid) return;
+    if (kSplit) {
+        const int64_t prow = ((int64_t)split * p.T + out_row) * p.Hq + head;
+        float *po = p.part_o + prow * kD;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                f32x4 x = {o[db][4 * gq], o[db][4 * gq + 1], o[db][4 * gq + 2], o[db][4 * gq + 3]};
+                *reinterpret_cast<f32x4 *>(po + db * 32 + 8 * gq + 4 * h) = x;
+            }
+        if (h == 0) {
+            p.part_ml[prow * 2] = m_run;
+            p.part_ml[prow * 2 + 1] = l_tot;
+        }
+    } else {
+        const float inv = 1.f / l_tot;
+        uint16_t *po = p.out + (out_row * p.Hq + head) * kD;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                bf16x4 x;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[e] = (__bf16)(o[db][4 * gq + e] * inv);
+                *reinterpret_cast<bf16x4 *>(po + db * 32 + 8 * gq + 4 * h) = x;
+            }
+    }
+}
+
+// out[row, head, :] = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max_s m_s).
+// 32 threads per (row, head), 4 consecutive d each.
+__global__ __launch_bounds__(256) void merge_splits_kernel(const float *__restrict__ part_o,
+                                                           const float *__restrict__ part_ml,
+                                                           uint16_t *__restrict__ out,
+                                                           int64_t n_rh, int nsplit)
+{
+    const int64_t rh = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);
+    if (rh >= n_rh) return;
+    const int d4 = (threadIdx.x & 31) * 4;
+    float m_star = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) {
+        const float *ml = part_ml + ((int64_t)s * n_rh + rh) * 2;
+        if (ml[1] > 0.f) m_star = fmaxf(m_star, ml[0]);
+    }
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float denom = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+        const float *ml = part_ml + ((int64_t)s * n_rh + rh) * 2;
+        const float ls = ml[1];
+        if (ls > 0.f) {
+            const float w = fast_exp2(ml[0] - m_star);
+            const f32x4 x = *reinterpret_cast<const f32x4 *>(part_o + ((int64_t)s * n_rh + rh) * kD + d4);
+            acc += x * w;
+            denom += ls * w;
+        }
+    }
+    const float inv = denom > 0.f ? 1.f / denom : 0.f;
+    bf16x4 y;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] = (__bf16)(acc[e] * inv);
+    *reinterpret_cast<bf16x4 *>(out + rh * kD + d4) = y;
+}
+
+// One workgroup copies 16 consecutive packed rows; one thread moves 16 bytes at a time.
+constexpr int kWriteRows = 16;
+__global__ __launch_bounds__(256) void write_kv_kernel(const uint16_t *__restrict__ k_new,
+                                                       const uint16_t *__restrict__ v_new,
+                                                       uint16_t *__restrict__ kv_pages,
+                                                       const int32_t *__restrict__ block_table,
+                                                       const int32_t *__restrict__ prefix_lens,
+                                                       const int32_t *__restrict__ extend_lens,
+                                                       int batch, int Hkv, int max_pages, int T)
+{
+    const int row0 = blockIdx.x * kWriteRows;
+    // request of the first row of the block
+    int r = 0, cu = 0;
+    while (r < batch && row0 >= cu + extend_lens[r]) {
+        cu += extend_lens[r];
+        ++r;
+    }
+    const int chunks_per_row = Hkv * 16; // 16-byte chunks of one row of k_new (or v_new)
+    const int total = kWriteRows * 2 * chunks_per_row;
+    for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
+        const int lr = idx / (2 * chunks_per_row);
+        int rest = idx - lr * 2 * chunks_per_row;
+        const int which = rest / chunks_per_row;
+        rest -= which * chunks_per_row;
+        const int g = rest >> 4;
+        const int ch = rest & 15;
+        const int row = row0 + lr;
+        if (row >= T) continue;
+        int rr = r, cc = cu;
+        while (rr < batch && row >= cc + extend_lens[rr]) {
+            cc += extend_lens[rr];
+            ++rr;
+        }
+        if (rr >= batch) continue;
+        const int tok = prefix_lens[rr] + (row - cc);
+        const int64_t page = block_table[(int64_t)rr * max_pages + (tok >> 4)];
+        const uint16_t *src = (which ? v_new : k_new) + ((int64_t)row * Hkv + g) * kD + ch * 8;
+        uint16_t *dst = kv_pages + ((((page * 2 + which) * Hkv + g) * kPS + (tok & 15)) * (int64_t)kD + ch * 8);
+        *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+    }
+}
+
+// ------------------------------------------------------------------ host side
+struct Plan {
+    int64_t q_tiles;   // sum_r ceil(E_r / kBM)
+    int32_t max_key_tiles;
+    int32_t nsplit;
+};
+
+int num_cus()
+{
+    static int cached = 0;
+    if (cached == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cached = n;
+    }
+    return cached;
+}
+
+int validate(const cp_shape *s)
+{
+    if (!s) return CP_ERR_NULL;
+    if (!s->h_prefix_lens || !s->h_extend_lens) return CP_ERR_NULL;
+    if (s->batch < 1 || s->num_q_heads < 1 || s->num_kv_heads < 1) return CP_ERR_SHAPE;
+    if (s->num_q_heads % s->num_kv_heads != 0) return CP_ERR_SHAPE;
+    if (s->head_dim != kD || s->page_size != kPS) return CP_ERR_SHAPE;
+    if (s->num_pages < 1 || s->max_pages_per_req < 1 || s->total_extend < 0) return CP_ERR_SHAPE;
+    if (!(s->softmax_scale > 0.f) || !(s->softmax_scale < 3.0e38f)) return CP_ERR_SHAPE;
+    if (s->num_splits < 0 || s->num_splits > kMaxSplits) return CP_ERR_SHAPE;
+    int64_t sum = 0;
+    for (int r = 0; r < s->batch; ++r) {
+        const int64_t P = s->h_prefix_lens[r], E = s->h_extend_lens[r];
+        if (P < 0 || E < 0) return CP_ERR_SHAPE;
+        if ((P + E + kPS - 1) / kPS > s->max_pages_per_req) return CP_ERR_SHAPE;
+        if (P + E > INT32_MAX - 2 * kBM) return CP_ERR_SHAPE;
+        sum += E;
+    }
+    if (sum != s->total_extend) return CP_ERR_SHAPE;
+    return CP_OK;
+}
+
+Plan make_plan(const cp_shape *s)
+{
+    Plan pl{0, 0, 1};
+    for (int r = 0; r < s->batch; ++r) {
+        const int64_t P = s->h_prefix_lens[r], E = s->h_extend_lens[r];
+        if (E == 0) continue;
+        pl.q_tiles += (E + kBM - 1) / kBM;
+        const int64_t kt = (P + kBN - 1) / kBN + (E + kBN - 1) / kBN;
+        if (kt > pl.max_key_tiles) pl.max_key_tiles = (int32_t)kt;
+    }
+    if (s->num_splits >= 1) {
+        pl.nsplit = s->num_splits;
+    } else {
+        // Split the keys only when the unsplit grid cannot give every CU two workgroups, and
+        // never into pieces shorter than 8 key tiles.
+        const int64_t items = pl.q_tiles * s->num_q_heads;
+        const int64_t want = 2LL * num_cus();
+        int64_t ns = 1;
+        if (items > 0 && items < want) ns = (want + items - 1) / items;
+        const int64_t cap = pl.max_key_tiles / 8;
+        if (ns > cap) ns = cap;
+        if (ns > kMaxSplits) ns = kMaxSplits;
+        if (ns < 1) ns = 1;
+        pl.nsplit = (int32_t)ns;
+    }
+    return pl;
+}
+
+size_t workspace_for(const cp_shape *s, const Plan &pl)
+{
+    if (pl.nsplit <= 1) return 0;
+    const size_t rows = (size_t)pl.nsplit * (size_t)s->total_extend * (size_t)s->num_q_heads;
+    size_t o_bytes = rows * kD * sizeof(float);
+    size_t ml_bytes = rows * 2 * sizeof(float);
+    return ((o_bytes + 255) / 256) * 256 + ((ml_bytes + 255) / 256) * 256;
+}
+
+} // namespace
+
+extern "C" {
+
+const char *cp_status_string(int status)
+{
+    switch (status) {
+    case CP_OK: return "ok";
+    case CP_ERR_NULL: return "a required pointer is NULL";
+    case CP_ERR_SHAPE: return "unsupported or inconsistent shape";
+    case CP_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
+    case CP_ERR_LAUNCH: return "HIP launch error";
+    default: return "unknown status";
+    }
+}
+
+int32_t cp_num_splits(const cp_shape *shape)
+{
+    if (validate(shape) != CP_OK) return 0;
+    return make_plan(shape).nsplit;
+}
+
+size_t cp_workspace_bytes(const cp_shape *shape)
+{
+    if (validate(shape) != CP_OK) return 0;
+    return workspace_for(shape, make_plan(shape));
+}
+
+int cp_extend_attention(const void *q, const void *k_new, const void *v_new, const void *kv_pages,
+                        const int32_t *block_table, const int32_t *prefix_lens,
+                        const int32_t *extend_lens, void *out, void *stream, const cp_shape *shape,
+                        void *workspace, size_t workspace_bytes)
+{
+    const int st = validate(shape);
+    if (st != CP_OK) return st;
+    if (!block_table || !prefix_lens || !extend_lens) return CP_ERR_NULL;
+    if (shape->total_extend == 0) return CP_OK;
+    if (!q || !k_new || !v_new || !kv_pages || !out) return CP_ERR_NULL;
+    const Plan pl = make_plan(shape);
+    const size_t need = workspace_for(shape, pl);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return CP_ERR_WORKSPACE;
+        if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return CP_ERR_WORKSPACE;
+    }
+    const int64_t per_head = pl.q_tiles * (shape->num_q_heads / shape->num_kv_heads) * pl.nsplit;
+    const int64_t total = per_head * shape->num_kv_heads;
+    if (total > INT32_MAX / 2) return CP_ERR_SHAPE;
+
+    AttnParams p;
+    p.q = static_cast<const uint16_t *>(q);
+    p.k_new = static_cast<const uint16_t *>(k_new);
+    p.v_new = static_cast<const uint16_t *>(v_new);
+    p.kv_pages = static_cast<const uint16_t *>(kv_pages);
+    p.block_table = block_table;
+    p.prefix_lens = prefix_lens;
+    p.extend_lens = extend_lens;
+    p.out = static_cast<uint16_t *>(out);
+    p.part_o = nullptr;
+    p.part_ml = nullptr;
+    p.batch = shape->batch;
+    p.Hq = shape->num_q_heads;
+    p.Hkv = shape->num_kv_heads;
+    p.G = shape->num_q_heads / shape->num_kv_heads;
+    p.max_pages = shape->max_pages_per_req;
+    p.T = shape->total_extend;
+    p.nsplit = pl.nsplit;
+    p.items_per_head = (int32_t)per_head;
+    p.total_items = (int32_t)total;
+    p.items_per_xcd = (int32_t)((total + kXcds - 1) / kXcds);
+    p.scale_log2 = shape->softmax_scale * 1.4426950408889634f;
+
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const dim3 grid((unsigned)(p.items_per_xcd * kXcds)), block(kThreads);
+    if (pl.nsplit > 1) {
+        const size_t rows = (size_t)pl.nsplit * (size_t)p.T * (size_t)p.Hq;
+        const size_t o_bytes = ((rows * kD * sizeof(float) + 255) / 256) * 256;
+        p.part_o = static_cast<float *>(workspace);
+        p.part_ml = reinterpret_cast<float *>(static_cast<char *>(workspace) + o_bytes);
+        hipLaunchKernelGGL(extend_attn_kernel<true>, grid, block, 0, hs, p);
+        if (hipGetLastError() != hipSuccess) return CP_ERR_LAUNCH;
+        const int64_t n_rh = (int64_t)p.T * p.Hq;
+        hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)((n_rh + 7) / 8)), dim3(256), 0, hs,
+                           p.part_o, p.part_ml, p.out, n_rh, pl.nsplit);
+    } else {
+        hipLaunchKernelGGL(extend_attn_kernel<false>, grid, block, 0, hs, p);
+    }
+    if (hipGetLastError() != hipSuccess) return CP_ERR_LAUNCH;
+    return CP_OK;
+}
+
+int cp_write_kv(const void *k_new, const void *v_new, void *kv_pages, const int32_t *block_table,
+                const int32_t *prefix_lens, const int32_t *extend_lens, void *stream,
+                const cp_shape *shape)
+{
+    const int st = validate(shape);
+    if (st != CP_OK) return st;
+    if (!block_table || !prefix_lens || !extend_lens) return CP_ERR_NULL;
+    if (shape->total_extend == 0) return CP_OK;
+    if (!k_new || !v_new || !kv_pages) return CP_ERR_NULL;
+    const int T = shape->total_extend;
+    const dim3 grid((unsigned)((T + kWriteRows - 1) / kWriteRows)), block(256);
+    hipLaunchKernelGGL(write_kv_kernel, grid, block, 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint16_t *>(k_new), static_cast<const uint16_t *>(v_new),
+                       static_cast<uint16_t *>(kv_pages), block_table, prefix_lens, extend_lens,
+                       shape->batch, shape->num_kv_heads, shape->max_pages_per_req, T);
+    if (hipGetLastError() != hipSuccess) return CP_ERR_LAUNCH;
+    return CP_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,210 @@
+"""GPU parity: the HIP path against the fp64 oracle on the same seeded inputs.
+
+Tolerances (bf16 inputs, fp32 accumulation, bf16 output): max-abs <= 2e-2 and mean-abs <= 2e-3
+over all compared elements, plus an error relative to the oracle's output RMS <= 2e-2, which
+stays meaningful at long context where the outputs themselves are ~1e-2.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+from helpers import error_stats
+from workloads import bf16_bits_to_f32, f32_to_bf16_bits
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, MEAN_ABS, REL_RMS = 2e-2, 2e-3, 2e-2
+
+
+def _check(got_bits, want, what=""):
+    got = bf16_bits_to_f32(got_bits).astype(np.float64)
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    st = error_stats(got, want)
+    print(f"[parity] {what}: {st}", flush=True)
+    assert st["max_abs"] <= MAX_ABS, (what, st)
+    assert st["mean_abs"] <= MEAN_ABS, (what, st)
+    assert st["rel_rms"] <= REL_RMS, (what, st)
+    return st
+
+
+@pytest.fixture(scope="module")
+def H():
+    import gpu_harness
+    return gpu_harness
+
+
+def test_config1_tiny_full(H):
+    w = W.config1_tiny()
+    _check(H.gpu_attention(w), oracle.attention_of(w), "config1")
+
+
+@pytest.mark.parametrize("P,E", [
+    ([45, 0, 300], [33, 257, 130]),      # ragged: partial pages, partial q tiles, P = 0
+    ([1, 63, 64, 65], [1, 127, 128, 129]),
+    ([16, 0, 5], [0, 1, 0]),             # empty requests
+    ([700], [391]),
+])
+def test_small_ragged_batches(H, P, E):
+    w = W.make_uniform("ragged", 101, len(P), 8, 2, P, E)
+    _check(H.gpu_attention(w), oracle.attention_of(w), f"ragged P={P} E={E}")
+
+
+@pytest.mark.parametrize("G,Hkv", [(1, 2), (2, 3), (8, 1)])
+def test_gqa_group_sizes(H, G, Hkv):
+    w = W.make_uniform("gqa", 102, 2, G * Hkv, Hkv, [130, 17], [70, 200])
+    _check(H.gpu_attention(w), oracle.attention_of(w), f"G={G} Hkv={Hkv}")
+
+
+@pytest.mark.parametrize("ns", [2, 3, 7, 64])
+def test_forced_split_k_matches_and_is_deterministic(H, ns):
+    w = W.make_uniform("split", 103, 2, 4, 2, [1000, 37], [300, 150])
+    want = oracle.attention_of(w)
+    a = H.gpu_attention(w, num_splits=ns)
+    _check(a, want, f"split={ns}")
+    b = H.gpu_attention(w, num_splits=ns)
+    np.testing.assert_array_equal(a, b)
+    # splitting only regroups fp32 partial sums
+    one = bf16_bits_to_f32(H.gpu_attention(w, num_splits=1)).astype(np.float64)
+    assert np.abs(bf16_bits_to_f32(a).astype(np.float64) - one).max() <= 1e-2
+
+
+def test_auto_split_on_short_extend(H):
+    import paper_2511_03475_amd as cp
+    w = W.make_uniform("short", 104, 2, 8, 2, 4096, 64)
+    case = H.DeviceCase(w)
+    assert cp.cp_num_splits(case.shape) > 1 and case.ws_bytes > 0
+    case.attention()
+    _check(case.out_bits(), oracle.attention_of(w), "auto split short extend")
+
+
+def test_write_kv_bit_exact_and_sentinel(H):
+    w = W.make_uniform("wkv", 105, 3, 4, 2, [5, 32, 0], [20, 1, 333], num_pages=40)
+    w.kv_pages[:] = 0x7FC1
+    case = H.DeviceCase(w)
+    case.write_kv()
+    want = oracle.write_kv(w.k_new, w.v_new, w.kv_pages, w.block_table, w.prefix_lens, w.extend_lens)
+    np.testing.assert_array_equal(case.pool_bits(), want)
+
+
+def test_write_then_extend_equals_one_pass(H):
+    N, Hq, Hkv = 600, 8, 2
+    full = W.make_uniform("seam", 106, 1, Hq, Hkv, 0, N, num_pages=40)
+    want = oracle.attention_of(full)
+    one_pass = H.gpu_attention(full)
+    _check(one_pass, want, "one pass")
+    for P in (1, 17, 64, 333, 599):
+        # cache the first P tokens with the GPU cache write, then extend with the rest
+        import copy
+        head = copy.copy(full)
+        head.prefix_lens = np.array([0], np.int32); head.extend_lens = np.array([P], np.int32)
+        head.q, head.k_new, head.v_new = full.q[:P], full.k_new[:P], full.v_new[:P]
+        hc = H.DeviceCase(head)
+        hc.write_kv()
+        tail = copy.copy(full)
+        tail.prefix_lens = np.array([P], np.int32); tail.extend_lens = np.array([N - P], np.int32)
+        tail.q, tail.k_new, tail.v_new = full.q[P:], full.k_new[P:], full.v_new[P:]
+        tail.kv_pages = hc.pool_bits()
+        got = H.gpu_attention(tail)
+        _check(got, want[P:], f"cache {P} then extend {N - P}")
+        d = np.abs(bf16_bits_to_f32(got).astype(np.float64) -
+                   bf16_bits_to_f32(one_pass[P:]).astype(np.float64))
+        assert d.max() <= 2e-2      # two bf16 roundings of values up to ~4
+
+
+def test_page_permutation_is_bitwise_invariant(H):
+    w = W.make_uniform("perm", 107, 2, 8, 2, [500, 130], [100, 200], num_pages=80)
+    base = H.gpu_attention(w)
+    perm = np.random.default_rng(1).permutation(w.num_pages)
+    import copy
+    w2 = copy.copy(w)
+    w2.kv_pages = np.empty_like(w.kv_pages); w2.kv_pages[perm] = w.kv_pages
+    w2.block_table = np.where(w.block_table >= 0, perm[np.maximum(w.block_table, 0)], -1).astype(np.int32)
+    np.testing.assert_array_equal(H.gpu_attention(w2), base)
+
+
+def _needle_case(P, E, Hq, Hkv, seed, n_needles):
+    """Every chosen row scores one key ~22 above all others: out must be that value row."""
+    w = W.make_uniform("needle", seed, 1, Hq, Hkv, P, E)
+    N, PS, D = P + E, 16, 128
+    nbits = max(int(N - 1).bit_length(), 1)
+    t_all = np.arange(N)
+    keys = np.zeros((N, D), np.float32)
+    for b in range(nbits):
+        keys[:, b] = np.where((t_all >> b) & 1, 8.0, -8.0)
+    vals = np.zeros((N, D), np.float32)
+    vals[:, 0] = t_all % 128; vals[:, 1] = (t_all // 128) % 128; vals[:, 2] = t_all // 16384
+    vals[:, 3] = 1.0
+    kb, vb = f32_to_bf16_bits(keys), f32_to_bf16_bits(vals)
+    pages = w.block_table[0, t_all[:P] // PS]
+    for g in range(Hkv):
+        w.kv_pages[pages, 0, g, t_all[:P] % PS] = kb[:P]
+        w.kv_pages[pages, 1, g, t_all[:P] % PS] = vb[:P]
+        w.k_new[:, g] = kb[P:]; w.v_new[:, g] = vb[P:]
+    rng = np.random.default_rng(seed)
+    rows = np.unique(np.concatenate([[0, E - 1], rng.integers(0, E, size=n_needles)]))
+    targets = np.array([int(rng.integers(0, P + i + 1)) for i in rows])
+    targets[0] = 0; targets[-1] = P + rows[-1]
+    # q = key(target) * c with c chosen so that the winner leads by 2*8*8*c*scale = 24
+    cq = 24.0 / (128.0 * w.softmax_scale)
+    w.q[:] = 0
+    for i, t in zip(rows, targets):
+        w.q[i, :] = f32_to_bf16_bits(keys[t] * np.float32(cq))
+    return w, rows, targets, bf16_bits_to_f32(vb).astype(np.float64)
+
+
+def test_needle_small(H):
+    w, rows, targets, vals = _needle_case(700, 300, 4, 2, 7, 64)
+    got = bf16_bits_to_f32(H.gpu_attention(w)).astype(np.float64)
+    for i, t in zip(rows, targets):
+        # the losers leak ~1e-5 in total; a wrong page would be off by >= 1
+        np.testing.assert_allclose(got[i], np.broadcast_to(vals[t], got[i].shape), rtol=0,
+                                   atol=1e-3, err_msg=f"row {i} target {t}")
+    # and the oracle agrees on what the needle rows hold
+    want = oracle.attention_of(w, rows=rows.astype(np.int32))
+    assert np.abs(want - vals[targets][:, None, :]).max() < 1e-6
+
+
+def test_value_ones_and_key_shift(H):
+    w = W.make_uniform("ones", 108, 1, 4, 2, 300, 200)
+    one = f32_to_bf16_bits(np.float32(1.0))
+    w.v_new[:] = one; w.kv_pages[:, 1] = one
+    got = bf16_bits_to_f32(H.gpu_attention(w, num_splits=3)).astype(np.float64)
+    assert np.abs(got - 1.0).max() <= 2 ** -7            # one bf16 ulp around 1
+    # large common score offset: keys shifted by a constant vector (scores reach +-100)
+    w = W.make_uniform("shift", 109, 1, 4, 2, 300, 200)
+    kf = bf16_bits_to_f32(w.k_new); kf[..., :4] = 64.0; w.k_new = f32_to_bf16_bits(kf)
+    pf = bf16_bits_to_f32(w.kv_pages[:, 0]); pf[..., :4] = 64.0; w.kv_pages[:, 0] = f32_to_bf16_bits(pf)
+    _check(H.gpu_attention(w), oracle.attention_of(w), "key shift")
+
+
+def test_error_paths_return_codes(H):
+    import paper_2511_03475_amd as cp
+    w = W.make_uniform("err", 110, 1, 4, 2, 32, 32)
+    case = H.DeviceCase(w, num_splits=2)
+    args = (case.q, case.k_new, case.v_new, case.kv_pages, case.block_table, case.prefix_lens,
+            case.extend_lens, case.out, None, case.shape)
+    assert cp.cp_extend_attention(*args, None, 0, check=False) == cp.CP_ERR_WORKSPACE
+    assert cp.cp_extend_attention(*args, case.workspace, case.ws_bytes - 1, check=False) == cp.CP_ERR_WORKSPACE
+    assert cp.cp_extend_attention(None, *args[1:], case.workspace, case.ws_bytes, check=False) == cp.CP_ERR_NULL
+    bad = cp.Shape(1, 4, 3, 128, 16, w.num_pages, w.max_pages_per_req, [32], [32], 0.1)
+    assert cp.cp_extend_attention(*args[:-1], bad, None, 0, check=False) == cp.CP_ERR_SHAPE
+    bad = cp.Shape(1, 4, 2, 64, 16, w.num_pages, w.max_pages_per_req, [32], [32], 0.1)
+    assert cp.cp_write_kv(case.k_new, case.v_new, case.kv_pages, case.block_table,
+                          case.prefix_lens, case.extend_lens, None, bad, check=False) == cp.CP_ERR_SHAPE
+    bad = cp.Shape(1, 4, 2, 128, 16, w.num_pages, 1, [32], [32], 0.1)   # table too narrow
+    assert cp.cp_extend_attention(*args[:-1], bad, None, 0, check=False) == cp.CP_ERR_SHAPE
+    with pytest.raises(cp.CpError):
+        cp.cp_extend_attention(*args, None, 0)
+
+
+# ------------------------------------------------------------ scaled-down shapes of configs 2, 3
+def test_config2_scaled_full_compare(H):
+    w = W.config2_rag_fixed(batch=3, block=128, Hq=8, Hkv=2, query=32, cached_region_pages=256)
+    _check(H.gpu_attention(w), oracle.attention_of(w), "config2 scaled")
+
+
+def test_config3_scaled_full_compare(H):
+    w = W.config3_rag_zipf(batch=12, block=64, topk=6, pool_ids=60, query=16, Hq=8, Hkv=2)
+    assert max(w.notes["matched_blocks"]) >= 1
+    _check(H.gpu_attention(w), oracle.attention_of(w), "config3 scaled")

@@ -44,15 +44,32 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def normal_bf16(rng: np.random.Generator, shape, chunk_elems: int = 1 << 24) -> np.ndarray:
-    """N(0,1) drawn in float32 and rounded once to bf16; chunked to bound memory."""
+def normal_bf16(rng: np.random.Generator, shape, chunk_elems: int = 1 << 23,
+                threads: int = 8) -> np.ndarray:
+    """N(0,1) drawn in float32 and rounded once to bf16.
+
+    The array is cut into fixed chunks, each filled from its own child generator, so the
+    result depends only on the seed and the shape, not on how many threads fill it.
+    """
     n = int(np.prod(shape, dtype=np.int64))
     out = np.empty(n, dtype=np.uint16)
-    pos = 0
-    while pos < n:
-        m = min(chunk_elems, n - pos)
-        out[pos:pos + m] = f32_to_bf16_bits(rng.standard_normal(m, dtype=np.float32))
-        pos += m
+    nchunks = (n + chunk_elems - 1) // chunk_elems
+    if nchunks == 0:
+        return out.reshape(shape)
+    children = rng.spawn(nchunks)
+
+    def fill(c):
+        lo = c * chunk_elems
+        hi = min(lo + chunk_elems, n)
+        out[lo:hi] = f32_to_bf16_bits(children[c].standard_normal(hi - lo, dtype=np.float32))
+
+    if nchunks == 1 or threads <= 1:
+        for c in range(nchunks):
+            fill(c)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            list(ex.map(fill, range(nchunks)))
     return out.reshape(shape)
 
 
