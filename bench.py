@@ -161,6 +161,8 @@ def main():
     ap.add_argument("--workload", default="long_context_32k")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only; use --gpus 1", file=sys.stderr)
@@ -172,6 +174,15 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     cp.load_library()   # raises if the HIP library has not been built
+
+    if args.copy_probe:
+        a = torch.empty(1 << 28, dtype=torch.int32, device="cuda:0").fill_(1)
+        b = torch.empty_like(a)
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+        torch.cuda.empty_cache()
 
     w, r, head = measure(args.workload, args.steps, args.warmup)
     cpu = None if args.no_cpu else cpu_baseline(w)
