@@ -6,7 +6,7 @@
 //                         (paper, Section 1 / Section 2.1: prefill over a prefix cache)
 //   merge_splits_kernel   combines split-K partial results
 //
-// Attention kernel layout.  One workgroup = 4 wavefronts = 128 query rows of one q head; each
+// Attention kernel layout.  One workgroup = 8 wavefronts = 256 query rows of one q head; each
 // wavefront owns 32 rows.  Keys are streamed in tiles of 64 through LDS.  Scores are computed
 // transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16 so that the accumulator lane
 // (lane % 32) is a query row: the softmax row reductions are then in-lane plus one exchange
@@ -22,9 +22,9 @@ namespace {
 
 constexpr int kD = 128;       // head dim
 constexpr int kPS = 16;       // tokens per page
-constexpr int kBM = 128;      // query rows per workgroup
+constexpr int kBM = 256;      // query rows per workgroup
 constexpr int kBN = 64;       // keys per tile
-constexpr int kThreads = 256; // 4 wavefronts
+constexpr int kThreads = 512; // 8 wavefronts
 constexpr int kXcds = 8;      // accelerator complex dies; workgroup ids round-robin over them
 constexpr int kMaxSplits = 64;
 
@@ -71,23 +71,28 @@ __device__ __forceinline__ float halfwave_sum(float x)
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// K/V tile of 64 keys, staged in registers between the global load and the LDS store.
+// K/V tile of 64 keys: each of the 512 threads stages two 16-byte chunks of K and two of V in
+// registers between the global load and the LDS store.
 struct TileRegs {
-    u32x4 k[4];
-    u32x4 v[4];
+    u32x4 k[2];
+    u32x4 v[2];
 };
 
+// LDS: two K buffers and three V buffers of one 64-key tile (16 KiB) each.  In iteration `it`
+// the wavefronts read K(it) and V(it-1) while tile it+1 is being written, so K needs two
+// buffers and V three for a single barrier per tile.
+constexpr int kTileBytes = kBN * kD * 2;
+constexpr int kLdsBytes = 5 * kTileBytes;
+
 template <bool kSplit>
-__global__ __launch_bounds__(kThreads, 2) void extend_attn_kernel(const AttnParams p)
+__global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams p)
 {
-    // 16-byte chunk c of key row r lives at chunk c ^ (r & 15) for K and c ^ ((r & 7) << 1)
-    // for V, which keeps both the row-per-lane K reads and the 8-row transposing V reads
-    // spread over all banks.
-    __shared__ __attribute__((aligned(16))) u32x4 lds_k[kBN * 16];
-    __shared__ __attribute__((aligned(16))) u32x4 lds_v[kBN * 16];
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    char *const lds_k = lds;                  // [2][64 rows][256 B]
+    char *const lds_v = lds + 2 * kTileBytes; // [3][64 rows][256 B]
 
     const int tid = threadIdx.x;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
     const int j = lane & 31; // query row within the wave; also key row / d row of A operands
     const int h = lane >> 5; // half-wave
@@ -121,10 +126,11 @@ __global__ __launch_bounds__(kThreads, 2) void extend_attn_kernel(const AttnPara
     if (r >= p.batch) return;
     const int P = p.prefix_lens[r];
 
-    const int q0 = t * kBM;                       // first extend row of the workgroup
-    const int row_i = q0 + wave * 32 + j;         // this lane's extend row (may be >= E)
-    const int rows_end = min(E, q0 + kBM);        // one past the last valid row of the tile
-    const int np_tiles = (P + kBN - 1) / kBN;     // prefix key tiles
+    const int q0 = t * kBM;                          // first extend row of the workgroup
+    const int wave_row0 = q0 + wave * 32;            // first extend row of this wavefront
+    const int row_i = wave_row0 + j;                 // this lane's extend row (may be >= E)
+    const int rows_end = min(E, q0 + kBM);           // one past the last valid row of the tile
+    const int np_tiles = (P + kBN - 1) / kBN;        // prefix key tiles
     const int ns_tiles = (rows_end + kBN - 1) / kBN; // suffix key tiles up to the diagonal
     const int n_tiles = np_tiles + ns_tiles;
     const int per_split = (n_tiles + p.nsplit - 1) / p.nsplit;
@@ -153,64 +159,77 @@ __global__ __launch_bounds__(kThreads, 2) void extend_attn_kernel(const AttnPara
             qf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qp + 16 * kk));
     }
 
-    // ---- addressing of this thread's share of a K/V tile: rows ld_row + 16 i, chunk ld_chunk
-    const int ld_row = tid >> 4;
-    const int ld_chunk = tid & 15;
+    // ---- this thread's share of a K/V tile: key rows ld_row and ld_row + 32, 16-byte chunk
+    // ld_chunk.  The four rows a wavefront loads per step share one page, so the block-table
+    // lookup and the page base are scalar.
+    const int ld_sub = lane >> 4;            // row within the wavefront's group of four
+    const int ld_row = wave * 4 + ld_sub;    // 0..31
+    const int ld_chunk = lane & 15;
     const int32_t *table = p.block_table + (int64_t)r * p.max_pages;
     const int64_t v_plane = (int64_t)p.Hkv * kPS * kD; // K slab -> V slab inside a page
 
     auto load_tile = [&](int kt, TileRegs &tr) {
-        const uint16_t *ks[4];
-        const uint16_t *vs[4];
+        const uint16_t *ks[2];
+        const uint16_t *vs[2];
         if (kt < np_tiles) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int tok = min(kt * kBN + i * 16 + ld_row, P - 1);
-                const int64_t page = table[tok >> 4];
-                ks[i] = p.kv_pages +
-                    (((page * 2 * p.Hkv + kvh) * kPS + (tok & 15)) * kD + ld_chunk * 8);
+            for (int i = 0; i < 2; ++i) {
+                const int tok0 = kt * kBN + i * 32 + wave * 4; // wave-uniform
+                const int64_t page = table[min(tok0, P - 1) >> 4];
+                const uint16_t *base = p.kv_pages + (page * 2 * p.Hkv + kvh) * (kPS * kD);
+                const int tok = min(tok0 + ld_sub, P - 1);
+                ks[i] = base + ((tok & 15) * kD + ld_chunk * 8);
                 vs[i] = ks[i] + v_plane;
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int srow = min((kt - np_tiles) * kBN + i * 16 + ld_row, E - 1);
+            for (int i = 0; i < 2; ++i) {
+                const int srow = min((kt - np_tiles) * kBN + i * 32 + ld_row, E - 1);
                 const int64_t off = ((int64_t)(cu + srow) * p.Hkv + kvh) * kD + ld_chunk * 8;
                 ks[i] = p.k_new + off;
                 vs[i] = p.v_new + off;
             }
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 2; ++i) {
             tr.k[i] = *(const __attribute__((address_space(1))) u32x4 *)(ks[i]);
             tr.v[i] = *(const __attribute__((address_space(1))) u32x4 *)(vs[i]);
         }
     };
-    auto store_tile = [&](const TileRegs &tr) {
+    // 16-byte chunk c of key row r is stored at chunk c ^ kswz(r) for K and c ^ vswz(r) for V:
+    //   kswz(r) = ((r & 7) << 1) | ((r >> 3) & 1)   16 consecutive rows -> 16 distinct chunks,
+    //                                               also for the two half-waves together
+    //   vswz(r) = (r & 3) << 2                      the four rows of a transposing read land in
+    //                                               four different 64-byte bank groups
+    const int st_kswz = ((ld_row & 7) << 1) | ((ld_row >> 3) & 1);
+    const int st_k = ld_row * 256 + ((ld_chunk ^ st_kswz) << 4);
+    const int st_v = ld_row * 256 + ((ld_chunk ^ ((ld_row & 3) << 2)) << 4);
+    auto store_tile = [&](const TileRegs &tr, int kbuf, int vbuf) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = i * 16 + ld_row;
-            lds_k[row * 16 + (ld_chunk ^ (row & 15))] = tr.k[i];
-            lds_v[row * 16 + (ld_chunk ^ ((row & 7) << 1))] = tr.v[i];
+        for (int i = 0; i < 2; ++i) {
+            *reinterpret_cast<u32x4 *>(lds_k + kbuf * kTileBytes + st_k + i * 32 * 256) = tr.k[i];
+            *reinterpret_cast<u32x4 *>(lds_v + vbuf * kTileBytes + st_v + i * 32 * 256) = tr.v[i];
         }
     };
 
-    // ---- per-lane LDS read offsets
+    // ---- per-lane LDS read offsets (bytes inside a tile buffer)
     // K, A operand of S^T: lane (j, h) reads 16 bytes of key row kb*32 + j at chunk 2 kk + h.
-    const int k_row_off = j * 16;   // in uint4 units, plus kb * 32 * 16
-    const int k_swz = j & 15;
+    int k_off[8];
+    {
+        const int kswz = ((j & 7) << 1) | ((j >> 3) & 1);
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) k_off[kk] = j * 256 + (((2 * kk + h) ^ kswz) << 4);
+    }
     // V^T, A operand of O^T = V^T P^T, through the transposing read: within a group of 16
     // lanes, lane i supplies the address of 4 consecutive d of key row k0 + i / 4 and receives
     // V[k0 .. k0+3][d0 + i].
-    const char *lds_v_bytes = reinterpret_cast<const char *>(lds_v);
-    int v_off[4]; // byte offset for d block db, before adding the key-row base
+    int v_off[4];
     {
-        const int vr = 4 * h + ((lane & 15) >> 2);  // key row modulo 8
-        const int swz = vr << 1;
+        const int vr = 4 * h + ((lane & 15) >> 2); // key row modulo 8
         const int c_lane = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
 #pragma unroll
         for (int db = 0; db < 4; ++db)
-            v_off[db] = vr * 256 + (((db * 4 + c_lane) ^ swz) << 4) + 8 * (lane & 1);
+            v_off[db] = vr * 256 + (((db * 4 + c_lane) ^ ((vr & 3) << 2)) << 4) + 8 * (lane & 1);
     }
 
     f32x16 o[4];
@@ -218,16 +237,110 @@ __global__ __launch_bounds__(kThreads, 2) void extend_attn_kernel(const AttnPara
     for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
-    float m_run = -INFINITY; // running row maximum, log2 domain (same in both half-waves)
+    float m_ref = -INFINITY; // reference maximum of the exponentials, log2 domain
     float l_run = 0.f;       // running sum over this half-wave's keys only
+    const float c = p.scale_log2;
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
+    // S^T = K Q^T for the tile in K buffer kbuf: two 32-key blocks x 32 query rows.
+    auto qk_tile = [&](int kbuf, f32x16 &s0, f32x16 &s1) {
+        const char *kb = lds_k + kbuf * kTileBytes;
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        s0 = zero;
+        s1 = zero;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            const u32x4 a0 = *reinterpret_cast<const u32x4 *>(kb + k_off[kk]);
+            const u32x4 a1 = *reinterpret_cast<const u32x4 *>(kb + k_off[kk] + 32 * 256);
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), qf[kk], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), qf[kk], s1, 0, 0, 0);
+        }
+    };
+    // O^T += V^T P^T for the tile in V buffer vbuf: 4 d blocks x 4 steps of 16 keys.
+    auto pv_tile = [&](int vbuf, const bf16x8 (&pb)[4]) {
+        const char *vb = lds_v + vbuf * kTileBytes;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) { // keys ks*16 .. ks*16+15
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                const char *a = vb + v_off[db] + ks * 16 * 256;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4 *)(a));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4 *)(a + 8 * 256));
+                const s16x8 vv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pb[ks], o[db], 0, 0, 0);
+            }
+        }
+    };
+    // Masks the keys of a boundary tile that the lane's row must not see.  Accumulator element
+    // v of block kb is key kb*32 + 8*(v/4) + 4*h + v%4 of the tile.
+    auto mask_tile = [&](int vis, f32x16 &s0, f32x16 &s1) {
+        const int vis_h = vis - 4 * h;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            if (8 * (v >> 2) + (v & 3) >= vis_h) s0[v] = -INFINITY;
+            if (32 + 8 * (v >> 2) + (v & 3) >= vis_h) s1[v] = -INFINITY;
+        }
+    };
+    // Online softmax of one tile, one query row per lane.  The reference maximum only moves
+    // when some row of the wavefront exceeds it by more than 8 (a factor 256), so that the
+    // rescale of O is rare; the exponentials then stay below 2^8.  Returns the bf16
+    // probabilities in B-operand order, the factor by which O and l must be scaled (applied by
+    // the caller once the previous tile's P V has been accumulated) and whether it is not 1.
+    auto softmax_tile = [&](const f32x16 &s0, const f32x16 &s1, bf16x8 (&pb)[4], float &alpha) -> bool {
+        float mx = fmaxf(fmaxf(s0[0], s0[1]), s0[2]);
+#pragma unroll
+        for (int v = 3; v < 15; v += 2) mx = fmaxf(fmaxf(mx, s0[v]), s0[v + 1]);
+        mx = fmaxf(fmaxf(mx, s0[15]), s1[0]);
+#pragma unroll
+        for (int v = 1; v < 15; v += 2) mx = fmaxf(fmaxf(mx, s1[v]), s1[v + 1]);
+        mx = fmaxf(mx, s1[15]);
+        mx = halfwave_max(mx);
+        const float m_new = fmaxf(m_ref, mx * c);
+        const bool move = __builtin_amdgcn_ballot_w64(m_new > m_ref + 8.f) != 0;
+        const float m_next = move ? m_new : m_ref;
+        const float m_use = (m_next == -INFINITY) ? 0.f : m_next;
+        alpha = fast_exp2(m_ref - m_use);
+        m_ref = m_next;
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            // pb[ks] element e is accumulator element 8*(ks&1)+e of block ks>>1
+            f32x2 x;
+            bf16x2 y;
+#define CP_EXP_PAIR(SRC, BASE, DST)                                                   \
+            x[0] = fast_exp2(fmaf(SRC[BASE + e], c, -m_use));                         \
+            x[1] = fast_exp2(fmaf(SRC[BASE + e + 1], c, -m_use));                     \
+            y = __builtin_convertvector(x, bf16x2);                                   \
+            psum = __builtin_amdgcn_fdot2_f32_bf16(y, ones, psum, false);             \
+            DST[e] = y[0];                                                            \
+            DST[e + 1] = y[1];
+            CP_EXP_PAIR(s0, 0, pb[0])
+            CP_EXP_PAIR(s0, 8, pb[1])
+            CP_EXP_PAIR(s1, 0, pb[2])
+            CP_EXP_PAIR(s1, 8, pb[3])
+#undef CP_EXP_PAIR
+        }
+        l_run = (move ? l_run * alpha : l_run) + psum;
+        return move;
+    };
+    auto rescale_o = [&](float alpha) {
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+    };
+
+    // ---- prologue: first tile into K buffer 0 / V buffer 0
     TileRegs tr;
     load_tile(kt_begin, tr);
-    store_tile(tr);
+    store_tile(tr, 0, 0);
     __syncthreads();
 
-    const float c = p.scale_log2;
-    const int wave_row0 = q0 + wave * 32;
+    bf16x8 pb_prev[4];   // probabilities of the previous tile, waiting for their P V
+    bool have_prev = false;
+    int kbuf = 0, vbuf = 0, vbuf_prev = 0;
 
     for (int kt = kt_begin; kt < kt_end; ++kt) {
         const bool has_next = kt + 1 < kt_end;
@@ -235,88 +348,41 @@ __global__ __launch_bounds__(kThreads, 2) void extend_attn_kernel(const AttnPara
 
         const bool suffix = kt >= np_tiles;
         const int key0 = suffix ? (kt - np_tiles) * kBN : kt * kBN; // first key of the tile
-        // suffix tile entirely above this wave's rows: nothing visible
+        // suffix tile entirely above this wavefront's rows: nothing visible, and the same
+        // holds for every later tile
         const bool skip = suffix && key0 > wave_row0 + 31;
         if (!skip) {
-            // ---- S^T = K Q^T : two 32-key blocks x 32 query rows
-            f32x16 s[2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
-#pragma unroll
-                for (int kk = 0; kk < 8; ++kk) {
-                    const u32x4 kraw = lds_k[kb * 32 * 16 + k_row_off + ((2 * kk + h) ^ k_swz)];
-                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8, kraw), qf[kk], s[kb], 0, 0, 0);
-                }
-            }
-            // ---- mask keys that are not visible (boundary tiles only)
-            // accumulator element v of block kb is key kb*32 + 8*(v/4) + 4*h + v%4
-            const int vis = suffix ? (row_i - key0 + 1) : (P - key0); // visible keys in tile
+            f32x16 s0, s1;
+            qk_tile(kbuf, s0, s1);
             const bool need_mask = suffix ? (key0 + kBN - 1 > wave_row0) : (key0 + kBN > P);
-            if (need_mask) {
-                const int vis_h = vis - 4 * h;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        if (kb * 32 + 8 * (v >> 2) + (v & 3) >= vis_h) s[kb][v] = -INFINITY;
-                    }
+            if (need_mask) mask_tile(suffix ? (row_i - key0 + 1) : (P - key0), s0, s1);
+            bf16x8 pb[4];
+            float alpha;
+            bool move;
+            if (have_prev) {
+                // softmax of this tile (VALU) next to P V of the previous one (MFMA)
+                move = softmax_tile(s0, s1, pb, alpha);
+                pv_tile(vbuf_prev, pb_prev);
+            } else {
+                move = softmax_tile(s0, s1, pb, alpha);
             }
-            // ---- online softmax, one query row per lane
-            float mx = s[0][0];
+            if (move) rescale_o(alpha);
 #pragma unroll
-            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[0][v]);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[1][v]);
-            mx = halfwave_max(mx);
-            const float m_new = fmaxf(m_run, mx * c);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
-                const float alpha = fast_exp2(m_run - m_use);
-                l_run *= alpha;
-#pragma unroll
-                for (int db = 0; db < 4; ++db)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
-                m_run = m_new;
-            }
-            float psum = 0.f;
-            bf16x8 pb[2][2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int mm = 0; mm < 2; ++mm)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float pv = fast_exp2(fmaf(s[kb][8 * mm + e], c, -m_use));
-                        psum += pv;
-                        pb[kb][mm][e] = (__bf16)pv;
-                    }
-            l_run += psum;
-            // ---- O^T += V^T P^T : 4 d blocks x 4 steps of 16 keys
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int mm = 0; mm < 2; ++mm) {
-                    const int krow_bytes = (kb * 32 + mm * 16) * 256;
-#pragma unroll
-                    for (int db = 0; db < 4; ++db) {
-                        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (__attribute__((address_space(3))) s16x4 *)(lds_v_bytes + v_off[db] + krow_bytes));
-                        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (__attribute__((address_space(3))) s16x4 *)(lds_v_bytes + v_off[db] + krow_bytes + 8 * 256));
-                        const s16x8 vv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, vv), pb[kb][mm], o[db], 0, 0, 0);
-                    }
-                }
+            for (int ks = 0; ks < 4; ++ks) pb_prev[ks] = pb[ks];
+            have_prev = true;
+        } else if (have_prev) {
+            pv_tile(vbuf_prev, pb_prev);
+            have_prev = false;
+        }
+        vbuf_prev = vbuf;
+        if (has_next) {
+            kbuf ^= 1;
+            vbuf = (vbuf == 2) ? 0 : vbuf + 1;
+            store_tile(tr, kbuf, vbuf);
         }
         __syncthreads();
-        if (has_next) store_tile(tr);
-        __syncthreads();
     }
+    if (have_prev) pv_tile(vbuf_prev, pb_prev);
 
     // ---- epilogue.  o[db][v] is O^T[d = db*32 + 8*(v/4) + 4*h + v%4][row j]
     const float l_tot = halfwave_sum(l_run);
@@ -332,7 +398,7 @@ __global__ __launch_bounds__(kThreads, 2) void extend_attn_kernel(const AttnPara
                 *reinterpret_cast<f32x4 *>(po + db * 32 + 8 * gq + 4 * h) = x;
             }
         if (h == 0) {
-            p.part_ml[prow * 2] = m_run;
+            p.part_ml[prow * 2] = m_ref;
             p.part_ml[prow * 2 + 1] = l_tot;
         }
     } else {
@@ -444,6 +510,20 @@ int num_cus()
         cached = n;
     }
     return cached;
+}
+
+// The attention kernel uses more LDS than the default per-workgroup limit; raise it once.
+bool allow_large_lds()
+{
+    static int state = 0; // 0 = not tried, 1 = ok, -1 = failed
+    if (state == 0) {
+        const hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void *>(&extend_attn_kernel<false>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        const hipError_t b = hipFuncSetAttribute(reinterpret_cast<const void *>(&extend_attn_kernel<true>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        state = (a == hipSuccess && b == hipSuccess) ? 1 : -1;
+    }
+    return state == 1;
 }
 
 int validate(const cp_shape *s)
@@ -576,6 +656,7 @@ int cp_extend_attention(const void *q, const void *k_new, const void *v_new, con
     p.items_per_xcd = (int32_t)((total + kXcds - 1) / kXcds);
     p.scale_log2 = shape->softmax_scale * 1.4426950408889634f;
 
+    if (!allow_large_lds()) return CP_ERR_LAUNCH;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)(p.items_per_xcd * kXcds)), block(kThreads);
     if (pl.nsplit > 1) {
@@ -583,13 +664,13 @@ int cp_extend_attention(const void *q, const void *k_new, const void *v_new, con
         const size_t o_bytes = ((rows * kD * sizeof(float) + 255) / 256) * 256;
         p.part_o = static_cast<float *>(workspace);
         p.part_ml = reinterpret_cast<float *>(static_cast<char *>(workspace) + o_bytes);
-        hipLaunchKernelGGL(extend_attn_kernel<true>, grid, block, 0, hs, p);
+        hipLaunchKernelGGL(extend_attn_kernel<true>, grid, block, kLdsBytes, hs, p);
         if (hipGetLastError() != hipSuccess) return CP_ERR_LAUNCH;
         const int64_t n_rh = (int64_t)p.T * p.Hq;
         hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)((n_rh + 7) / 8)), dim3(256), 0, hs,
                            p.part_o, p.part_ml, p.out, n_rh, pl.nsplit);
     } else {
-        hipLaunchKernelGGL(extend_attn_kernel<false>, grid, block, 0, hs, p);
+        hipLaunchKernelGGL(extend_attn_kernel<false>, grid, block, kLdsBytes, hs, p);
     }
     if (hipGetLastError() != hipSuccess) return CP_ERR_LAUNCH;
     return CP_OK;
