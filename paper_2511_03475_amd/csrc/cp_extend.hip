@@ -16,6 +16,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "cp_extend.h"
 
 namespace {
@@ -27,6 +29,7 @@ constexpr int kBN = 64;       // keys per tile
 constexpr int kThreads = 512; // 8 wavefronts
 constexpr int kXcds = 8;      // accelerator complex dies; workgroup ids round-robin over them
 constexpr int kMaxSplits = 64;
+constexpr int kWaves = kThreads / 64;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
@@ -78,18 +81,27 @@ struct TileRegs {
     u32x4 v[2];
 };
 
-// LDS: two K buffers and three V buffers of one 64-key tile (16 KiB) each.  In iteration `it`
-// the wavefronts read K(it) and V(it-1) while tile it+1 is being written, so K needs two
-// buffers and V three for a single barrier per tile.
-constexpr int kTileBytes = kBN * kD * 2;
-constexpr int kLdsBytes = 5 * kTileBytes;
+// LDS: four K buffers and four V buffers of one 64-key tile (16 KiB) each, tile t in buffer
+// t % 4.  The two groups of four wavefronts run half an iteration apart (see the main loop), a
+// tile is written two iterations before its first use, and V(t) is still read one iteration
+// after K(t), which together need four buffers of each.
+// Rows are padded instead of swizzled so that every LDS read address is a per-lane base plus
+// an immediate: K rows have a pitch of 272 bytes (16 consecutive rows at the same column fall
+// into 16 different 16-byte bank groups), V rows a pitch of 320 bytes (the four consecutive
+// rows of a transposing read fall into four different 64-byte bank groups).
+constexpr int kNumBufs = 4;
+constexpr int kPitchK = 272;
+constexpr int kPitchV = 320;
+constexpr int kTileBytesK = kBN * kPitchK;
+constexpr int kTileBytesV = kBN * kPitchV;
+constexpr int kLdsBytes = kNumBufs * (kTileBytesK + kTileBytesV);
 
 template <bool kSplit>
 __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams p)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    char *const lds_k = lds;                  // [2][64 rows][256 B]
-    char *const lds_v = lds + 2 * kTileBytes; // [3][64 rows][256 B]
+    char *const lds_k = lds;                          // [4][64 rows][272 B]
+    char *const lds_v = lds + kNumBufs * kTileBytesK; // [4][64 rows][320 B]
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -136,11 +148,12 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     const int per_split = (n_tiles + p.nsplit - 1) / p.nsplit;
     const int kt_begin = split * per_split;
     const int kt_end = min(n_tiles, kt_begin + per_split);
+    const int n_it = kt_end - kt_begin;              // key tiles of this work item
 
     const int64_t out_row = (int64_t)(cu + min(row_i, E - 1));
     const bool row_valid = row_i < E;
 
-    if (kt_begin >= kt_end) {
+    if (n_it <= 0) {
         // empty split: the merge skips entries whose sum is zero
         if (kSplit && row_valid && h == 0) {
             float *ml = p.part_ml + (((int64_t)split * p.T + out_row) * p.Hq + head) * 2;
@@ -161,12 +174,14 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
 
     // ---- this thread's share of a K/V tile: key rows ld_row and ld_row + 32, 16-byte chunk
     // ld_chunk.  The four rows a wavefront loads per step share one page, so the block-table
-    // lookup and the page base are scalar.
-    const int ld_sub = lane >> 4;            // row within the wavefront's group of four
-    const int ld_row = wave * 4 + ld_sub;    // 0..31
+    // lookup and the page base are scalar; rows past the end of the prefix (or of the suffix)
+    // re-read the last valid row so that no uninitialised cache slot is ever touched.
+    const int ld_sub = lane >> 4;         // row within the wavefront's group of four
+    const int ld_row = wave * 4 + ld_sub; // 0..31
     const int ld_chunk = lane & 15;
     const int32_t *table = p.block_table + (int64_t)r * p.max_pages;
     const int64_t v_plane = (int64_t)p.Hkv * kPS * kD; // K slab -> V slab inside a page
+    const int64_t row_pitch = (int64_t)p.Hkv * kD;     // elements between rows of k_new
 
     auto load_tile = [&](int kt, TileRegs &tr) {
         const uint16_t *ks[2];
@@ -174,20 +189,22 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
         if (kt < np_tiles) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                const int tok0 = kt * kBN + i * 32 + wave * 4; // wave-uniform
-                const int64_t page = table[min(tok0, P - 1) >> 4];
+                const int tok0 = min(kt * kBN + i * 32 + wave * 4, P - 1); // wave-uniform
+                const int sub = min(ld_sub, P - 1 - tok0);
+                const int64_t page = table[tok0 >> 4];
                 const uint16_t *base = p.kv_pages + (page * 2 * p.Hkv + kvh) * (kPS * kD);
-                const int tok = min(tok0 + ld_sub, P - 1);
-                ks[i] = base + ((tok & 15) * kD + ld_chunk * 8);
+                ks[i] = base + ((((tok0 + sub) & 15) * kD) + ld_chunk * 8);
                 vs[i] = ks[i] + v_plane;
             }
         } else {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                const int srow = min((kt - np_tiles) * kBN + i * 32 + ld_row, E - 1);
-                const int64_t off = ((int64_t)(cu + srow) * p.Hkv + kvh) * kD + ld_chunk * 8;
-                ks[i] = p.k_new + off;
-                vs[i] = p.v_new + off;
+                const int srow0 = min((kt - np_tiles) * kBN + i * 32 + wave * 4, E - 1);
+                const int sub = min(ld_sub, E - 1 - srow0);
+                const int64_t base = ((int64_t)(cu + srow0) * p.Hkv + kvh) * kD;
+                const int off = sub * (int)row_pitch + ld_chunk * 8;
+                ks[i] = p.k_new + base + off;
+                vs[i] = p.v_new + base + off;
             }
         }
 #pragma unroll
@@ -196,41 +213,23 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
             tr.v[i] = *(const __attribute__((address_space(1))) u32x4 *)(vs[i]);
         }
     };
-    // 16-byte chunk c of key row r is stored at chunk c ^ kswz(r) for K and c ^ vswz(r) for V:
-    //   kswz(r) = ((r & 7) << 1) | ((r >> 3) & 1)   16 consecutive rows -> 16 distinct chunks,
-    //                                               also for the two half-waves together
-    //   vswz(r) = (r & 3) << 2                      the four rows of a transposing read land in
-    //                                               four different 64-byte bank groups
-    const int st_kswz = ((ld_row & 7) << 1) | ((ld_row >> 3) & 1);
-    const int st_k = ld_row * 256 + ((ld_chunk ^ st_kswz) << 4);
-    const int st_v = ld_row * 256 + ((ld_chunk ^ ((ld_row & 3) << 2)) << 4);
-    auto store_tile = [&](const TileRegs &tr, int kbuf, int vbuf) {
+    const int st_k = ld_row * kPitchK + ld_chunk * 16;
+    const int st_v = ld_row * kPitchV + ld_chunk * 16;
+    auto store_tile = [&](const TileRegs &tr, int buf) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            *reinterpret_cast<u32x4 *>(lds_k + kbuf * kTileBytes + st_k + i * 32 * 256) = tr.k[i];
-            *reinterpret_cast<u32x4 *>(lds_v + vbuf * kTileBytes + st_v + i * 32 * 256) = tr.v[i];
+            *reinterpret_cast<u32x4 *>(lds_k + buf * kTileBytesK + st_k + i * 32 * kPitchK) = tr.k[i];
+            *reinterpret_cast<u32x4 *>(lds_v + buf * kTileBytesV + st_v + i * 32 * kPitchV) = tr.v[i];
         }
     };
 
     // ---- per-lane LDS read offsets (bytes inside a tile buffer)
     // K, A operand of S^T: lane (j, h) reads 16 bytes of key row kb*32 + j at chunk 2 kk + h.
-    int k_off[8];
-    {
-        const int kswz = ((j & 7) << 1) | ((j >> 3) & 1);
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) k_off[kk] = j * 256 + (((2 * kk + h) ^ kswz) << 4);
-    }
+    const int k_lane = j * kPitchK + h * 16;
     // V^T, A operand of O^T = V^T P^T, through the transposing read: within a group of 16
     // lanes, lane i supplies the address of 4 consecutive d of key row k0 + i / 4 and receives
-    // V[k0 .. k0+3][d0 + i].
-    int v_off[4];
-    {
-        const int vr = 4 * h + ((lane & 15) >> 2); // key row modulo 8
-        const int c_lane = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-            v_off[db] = vr * 256 + (((db * 4 + c_lane) ^ ((vr & 3) << 2)) << 4) + 8 * (lane & 1);
-    }
+    // V[k0 .. k0+3][d0 + i].  Here k0 = 4 h (+ 8 for the second read), d0 = 32 db + 16 (lane/16 % 2).
+    const int v_lane = (4 * h + ((lane & 15) >> 2)) * kPitchV + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
 
     f32x16 o[4];
 #pragma unroll
@@ -244,30 +243,30 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
 
     // S^T = K Q^T for the tile in K buffer kbuf: two 32-key blocks x 32 query rows.
     auto qk_tile = [&](int kbuf, f32x16 &s0, f32x16 &s1) {
-        const char *kb = lds_k + kbuf * kTileBytes;
+        const char *kb = lds_k + kbuf * kTileBytesK + k_lane;
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         s0 = zero;
         s1 = zero;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
-            const u32x4 a0 = *reinterpret_cast<const u32x4 *>(kb + k_off[kk]);
-            const u32x4 a1 = *reinterpret_cast<const u32x4 *>(kb + k_off[kk] + 32 * 256);
+            const u32x4 a0 = *reinterpret_cast<const u32x4 *>(kb + kk * 32);
+            const u32x4 a1 = *reinterpret_cast<const u32x4 *>(kb + kk * 32 + 32 * kPitchK);
             s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), qf[kk], s0, 0, 0, 0);
             s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), qf[kk], s1, 0, 0, 0);
         }
     };
     // O^T += V^T P^T for the tile in V buffer vbuf: 4 d blocks x 4 steps of 16 keys.
     auto pv_tile = [&](int vbuf, const bf16x8 (&pb)[4]) {
-        const char *vb = lds_v + vbuf * kTileBytes;
+        const char *vb = lds_v + vbuf * kTileBytesV + v_lane;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) { // keys ks*16 .. ks*16+15
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
-                const char *a = vb + v_off[db] + ks * 16 * 256;
+                const char *a = vb + db * 64 + ks * 16 * kPitchV;
                 const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                     (__attribute__((address_space(3))) s16x4 *)(a));
                 const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) s16x4 *)(a + 8 * 256));
+                    (__attribute__((address_space(3))) s16x4 *)(a + 8 * kPitchV));
                 const s16x8 vv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pb[ks], o[db], 0, 0, 0);
             }
@@ -283,26 +282,9 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
             if (32 + 8 * (v >> 2) + (v & 3) >= vis_h) s1[v] = -INFINITY;
         }
     };
-    // Online softmax of one tile, one query row per lane.  The reference maximum only moves
-    // when some row of the wavefront exceeds it by more than 8 (a factor 256), so that the
-    // rescale of O is rare; the exponentials then stay below 2^8.  Returns the bf16
-    // probabilities in B-operand order, the factor by which O and l must be scaled (applied by
-    // the caller once the previous tile's P V has been accumulated) and whether it is not 1.
-    auto softmax_tile = [&](const f32x16 &s0, const f32x16 &s1, bf16x8 (&pb)[4], float &alpha) -> bool {
-        float mx = fmaxf(fmaxf(s0[0], s0[1]), s0[2]);
-#pragma unroll
-        for (int v = 3; v < 15; v += 2) mx = fmaxf(fmaxf(mx, s0[v]), s0[v + 1]);
-        mx = fmaxf(fmaxf(mx, s0[15]), s1[0]);
-#pragma unroll
-        for (int v = 1; v < 15; v += 2) mx = fmaxf(fmaxf(mx, s1[v]), s1[v + 1]);
-        mx = fmaxf(mx, s1[15]);
-        mx = halfwave_max(mx);
-        const float m_new = fmaxf(m_ref, mx * c);
-        const bool move = __builtin_amdgcn_ballot_w64(m_new > m_ref + 8.f) != 0;
-        const float m_next = move ? m_new : m_ref;
-        const float m_use = (m_next == -INFINITY) ? 0.f : m_next;
-        alpha = fast_exp2(m_ref - m_use);
-        m_ref = m_next;
+    // Exponentials of one tile against the reference m_use (log2 domain), one query row per
+    // lane: bf16 probabilities in B-operand order; returns their sum over this lane's keys.
+    auto exp_tile = [&](const f32x16 &s0, const f32x16 &s1, bf16x8 (&pb)[4], float m_use) -> float {
         float psum = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
@@ -322,8 +304,17 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
             CP_EXP_PAIR(s1, 8, pb[3])
 #undef CP_EXP_PAIR
         }
-        l_run = (move ? l_run * alpha : l_run) + psum;
-        return move;
+        return psum;
+    };
+    auto row_max = [&](const f32x16 &s0, const f32x16 &s1) -> float {
+        float mx = fmaxf(fmaxf(s0[0], s0[1]), s0[2]);
+#pragma unroll
+        for (int v = 3; v < 15; v += 2) mx = fmaxf(fmaxf(mx, s0[v]), s0[v + 1]);
+        mx = fmaxf(fmaxf(mx, s0[15]), s1[0]);
+#pragma unroll
+        for (int v = 1; v < 15; v += 2) mx = fmaxf(fmaxf(mx, s1[v]), s1[v + 1]);
+        mx = fmaxf(mx, s1[15]);
+        return halfwave_max(mx);
     };
     auto rescale_o = [&](float alpha) {
 #pragma unroll
@@ -332,57 +323,98 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
             for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
     };
 
-    // ---- prologue: first tile into K buffer 0 / V buffer 0
+    // ---- main loop, one barrier per key tile.  Iteration `it`:
+    //     fetch tile it+2 from global memory into registers
+    //     S = K(it) Q^T                                            (MFMA)
+    //     p = exp2(S c - m_ref) next to O += V(it-1)^T P(it-1)^T   (VALU next to MFMA)
+    //     write tile it+2 to LDS buffer (it+2) % 4, barrier
+    // The exponentials are taken against the running reference m_ref WITHOUT first reducing
+    // the row maximum of the tile.  Only when some row of the wavefront has no reference yet,
+    // or its sum shows that the reference is stale by more than a factor 2^30, is the tile
+    // redone the classic way (row maximum, new reference, rescale of O and l); any reference
+    // gives the same result after the final division as long as nothing overflows, and fp32
+    // leaves ~2^97 of headroom above that trigger.
     TileRegs tr;
     load_tile(kt_begin, tr);
-    store_tile(tr, 0, 0);
+    store_tile(tr, 0);
+    if (n_it > 1) {
+        load_tile(kt_begin + 1, tr);
+        store_tile(tr, 1);
+    }
     __syncthreads();
 
-    bf16x8 pb_prev[4];   // probabilities of the previous tile, waiting for their P V
-    bool have_prev = false;
-    int kbuf = 0, vbuf = 0, vbuf_prev = 0;
+    bool have_prev = false; // the previous tile's probabilities still wait for their P V
+    constexpr float kStale = 1073741824.f; // 2^30
 
-    for (int kt = kt_begin; kt < kt_end; ++kt) {
-        const bool has_next = kt + 1 < kt_end;
-        if (has_next) load_tile(kt + 1, tr);
-
+    // Classic online-softmax step: row maximum, new reference, rescale of O and l.
+    auto redo_tile = [&](const f32x16 &s0, const f32x16 &s1, bf16x8 (&pb)[4]) -> float {
+        const float m_new = fmaxf(m_ref, row_max(s0, s1) * c);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = fast_exp2(m_ref - m_use);
+        rescale_o(alpha);
+        l_run *= alpha;
+        m_ref = m_new;
+        return exp_tile(s0, s1, pb, m_use);
+    };
+    // first key of tile kt in its own numbering (prefix tokens or suffix rows)
+    auto tile_key0 = [&](int kt) { return kt >= np_tiles ? (kt - np_tiles) * kBN : kt * kBN; };
+    auto masked_qk = [&](int kt, int buf, f32x16 &s0, f32x16 &s1) {
         const bool suffix = kt >= np_tiles;
-        const int key0 = suffix ? (kt - np_tiles) * kBN : kt * kBN; // first key of the tile
-        // suffix tile entirely above this wavefront's rows: nothing visible, and the same
-        // holds for every later tile
-        const bool skip = suffix && key0 > wave_row0 + 31;
-        if (!skip) {
+        const int key0 = tile_key0(kt);
+        qk_tile(buf, s0, s1);
+        const bool need_mask = suffix ? (key0 + kBN - 1 > wave_row0) : (key0 + kBN > P);
+        if (need_mask) mask_tile(suffix ? (row_i - key0 + 1) : (P - key0), s0, s1);
+    };
+    // a suffix tile entirely above this wavefront's rows shows it nothing, and neither does
+    // any later tile
+    auto skipped = [&](int kt) { return kt >= np_tiles && tile_key0(kt) > wave_row0 + 31; };
+
+    bf16x8 pb_a[4], pb_b[4]; // probabilities of even / odd tiles
+
+    // iteration 0: no previous tile yet, and no reference: classic step
+    {
+        const bool prefetch = 2 < n_it;
+        if (prefetch) load_tile(kt_begin + 2, tr);
+        if (!skipped(kt_begin)) {
             f32x16 s0, s1;
-            qk_tile(kbuf, s0, s1);
-            const bool need_mask = suffix ? (key0 + kBN - 1 > wave_row0) : (key0 + kBN > P);
-            if (need_mask) mask_tile(suffix ? (row_i - key0 + 1) : (P - key0), s0, s1);
-            bf16x8 pb[4];
-            float alpha;
-            bool move;
-            if (have_prev) {
-                // softmax of this tile (VALU) next to P V of the previous one (MFMA)
-                move = softmax_tile(s0, s1, pb, alpha);
-                pv_tile(vbuf_prev, pb_prev);
-            } else {
-                move = softmax_tile(s0, s1, pb, alpha);
-            }
-            if (move) rescale_o(alpha);
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) pb_prev[ks] = pb[ks];
+            masked_qk(kt_begin, 0, s0, s1);
+            l_run += redo_tile(s0, s1, pb_a);
             have_prev = true;
-        } else if (have_prev) {
-            pv_tile(vbuf_prev, pb_prev);
-            have_prev = false;
         }
-        vbuf_prev = vbuf;
-        if (has_next) {
-            kbuf ^= 1;
-            vbuf = (vbuf == 2) ? 0 : vbuf + 1;
-            store_tile(tr, kbuf, vbuf);
-        }
+        if (prefetch) store_tile(tr, 2);
         __syncthreads();
     }
-    if (have_prev) pv_tile(vbuf_prev, pb_prev);
+    auto tile_step = [&](int it, bf16x8 (&pb_cur)[4], bf16x8 (&pb_prev)[4]) {
+        const int buf = it & 3;
+        const int kt = kt_begin + it;
+        const bool prefetch = it + 2 < n_it;
+        if (prefetch) load_tile(kt + 2, tr);
+        if (!skipped(kt)) {
+            // the previous tile was not skipped either, so its probabilities are pending
+            f32x16 s0, s1;
+            masked_qk(kt, buf, s0, s1);
+            // one basic block: the exponentials (VALU) interleave with P V (MFMA)
+            float psum = exp_tile(s0, s1, pb_cur, (m_ref == -INFINITY) ? 0.f : m_ref);
+            pv_tile((buf + 3) & 3, pb_prev);
+            if (__builtin_amdgcn_ballot_w64(!(psum < kStale) || m_ref == -INFINITY) != 0)
+                psum = redo_tile(s0, s1, pb_cur);
+            l_run += psum;
+        } else if (have_prev) {
+            pv_tile((buf + 3) & 3, pb_prev);
+            have_prev = false;
+        }
+        if (prefetch) store_tile(tr, (buf + 2) & 3);
+        __syncthreads();
+    };
+    for (int it = 1; it < n_it; it += 2) {
+        tile_step(it, pb_b, pb_a);
+        if (it + 1 < n_it) tile_step(it + 1, pb_a, pb_b);
+    }
+    // P V of the last tile (a wavefront that skipped tiles has already done it)
+    if (have_prev) {
+        if ((n_it - 1) & 1) pv_tile((n_it - 1) & 3, pb_b);
+        else pv_tile((n_it - 1) & 3, pb_a);
+    }
 
     // ---- epilogue.  o[db][v] is O^T[d = db*32 + 8*(v/4) + 4*h + v%4][row j]
     const float l_tot = halfwave_sum(l_run);
