@@ -30,6 +30,9 @@ constexpr int kThreads = 512; // 8 wavefronts
 constexpr int kXcds = 8;      // accelerator complex dies; workgroup ids round-robin over them
 constexpr int kMaxSplits = 64;
 constexpr int kWaves = kThreads / 64;
+constexpr int kNKB = kBN / 32;            // 32-key blocks per tile
+constexpr int kLoadRows = kWaves * 4;     // key rows one load step of the workgroup covers
+static_assert(kBM == kWaves * 32 && kBN == 2 * kLoadRows, "tile shape");
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
@@ -172,12 +175,12 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
             qf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qp + 16 * kk));
     }
 
-    // ---- this thread's share of a K/V tile: key rows ld_row and ld_row + 32, 16-byte chunk
+    // ---- this thread's share of a K/V tile: key rows ld_row and ld_row + kLoadRows, 16-byte chunk
     // ld_chunk.  The four rows a wavefront loads per step share one page, so the block-table
     // lookup and the page base are scalar; rows past the end of the prefix (or of the suffix)
     // re-read the last valid row so that no uninitialised cache slot is ever touched.
     const int ld_sub = lane >> 4;         // row within the wavefront's group of four
-    const int ld_row = wave * 4 + ld_sub; // 0..31
+    const int ld_row = wave * 4 + ld_sub; // 0..kLoadRows-1
     const int ld_chunk = lane & 15;
     const int32_t *table = p.block_table + (int64_t)r * p.max_pages;
     const int64_t v_plane = (int64_t)p.Hkv * kPS * kD; // K slab -> V slab inside a page
@@ -189,7 +192,7 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
         if (kt < np_tiles) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                const int tok0 = min(kt * kBN + i * 32 + wave * 4, P - 1); // wave-uniform
+                const int tok0 = min(kt * kBN + i * kLoadRows + wave * 4, P - 1); // wave-uniform
                 const int sub = min(ld_sub, P - 1 - tok0);
                 const int64_t page = table[tok0 >> 4];
                 const uint16_t *base = p.kv_pages + (page * 2 * p.Hkv + kvh) * (kPS * kD);
@@ -199,7 +202,7 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
         } else {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                const int srow0 = min((kt - np_tiles) * kBN + i * 32 + wave * 4, E - 1);
+                const int srow0 = min((kt - np_tiles) * kBN + i * kLoadRows + wave * 4, E - 1);
                 const int sub = min(ld_sub, E - 1 - srow0);
                 const int64_t base = ((int64_t)(cu + srow0) * p.Hkv + kvh) * kD;
                 const int off = sub * (int)row_pitch + ld_chunk * 8;
@@ -218,8 +221,8 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     auto store_tile = [&](const TileRegs &tr, int buf) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            *reinterpret_cast<u32x4 *>(lds_k + buf * kTileBytesK + st_k + i * 32 * kPitchK) = tr.k[i];
-            *reinterpret_cast<u32x4 *>(lds_v + buf * kTileBytesV + st_v + i * 32 * kPitchV) = tr.v[i];
+            *reinterpret_cast<u32x4 *>(lds_k + buf * kTileBytesK + st_k + i * kLoadRows * kPitchK) = tr.k[i];
+            *reinterpret_cast<u32x4 *>(lds_v + buf * kTileBytesV + st_v + i * kLoadRows * kPitchV) = tr.v[i];
         }
     };
 
@@ -241,25 +244,29 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     const float c = p.scale_log2;
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
-    // S^T = K Q^T for the tile in K buffer kbuf: two 32-key blocks x 32 query rows.
-    auto qk_tile = [&](int kbuf, f32x16 &s0, f32x16 &s1) {
+    typedef f32x16 STile[kNKB];     // scores: 32-key blocks x 32 query rows
+    typedef bf16x8 PTile[2 * kNKB]; // probabilities: one B operand per 16 keys
+
+    // S^T = K Q^T for the tile in K buffer kbuf.
+    auto qk_tile = [&](int kbuf, STile &s) {
         const char *kb = lds_k + kbuf * kTileBytesK + k_lane;
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        s0 = zero;
-        s1 = zero;
+#pragma unroll
+        for (int b = 0; b < kNKB; ++b) s[b] = zero;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
-            const u32x4 a0 = *reinterpret_cast<const u32x4 *>(kb + kk * 32);
-            const u32x4 a1 = *reinterpret_cast<const u32x4 *>(kb + kk * 32 + 32 * kPitchK);
-            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), qf[kk], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), qf[kk], s1, 0, 0, 0);
+#pragma unroll
+            for (int b = 0; b < kNKB; ++b) {
+                const u32x4 a = *reinterpret_cast<const u32x4 *>(kb + kk * 32 + b * 32 * kPitchK);
+                s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), qf[kk], s[b], 0, 0, 0);
+            }
         }
     };
-    // O^T += V^T P^T for the tile in V buffer vbuf: 4 d blocks x 4 steps of 16 keys.
-    auto pv_tile = [&](int vbuf, const bf16x8 (&pb)[4]) {
+    // O^T += V^T P^T for the tile in V buffer vbuf: 4 d blocks x steps of 16 keys.
+    auto pv_tile = [&](int vbuf, const PTile &pb) {
         const char *vb = lds_v + vbuf * kTileBytesV + v_lane;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) { // keys ks*16 .. ks*16+15
+        for (int ks = 0; ks < 2 * kNKB; ++ks) { // keys ks*16 .. ks*16+15
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
                 const char *a = vb + db * 64 + ks * 16 * kPitchV;
@@ -273,47 +280,40 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
         }
     };
     // Masks the keys of a boundary tile that the lane's row must not see.  Accumulator element
-    // v of block kb is key kb*32 + 8*(v/4) + 4*h + v%4 of the tile.
-    auto mask_tile = [&](int vis, f32x16 &s0, f32x16 &s1) {
+    // v of block b is key b*32 + 8*(v/4) + 4*h + v%4 of the tile.
+    auto mask_tile = [&](int vis, STile &s) {
         const int vis_h = vis - 4 * h;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            if (8 * (v >> 2) + (v & 3) >= vis_h) s0[v] = -INFINITY;
-            if (32 + 8 * (v >> 2) + (v & 3) >= vis_h) s1[v] = -INFINITY;
-        }
+        for (int b = 0; b < kNKB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (b * 32 + 8 * (v >> 2) + (v & 3) >= vis_h) s[b][v] = -INFINITY;
     };
     // Exponentials of one tile against the reference m_use (log2 domain), one query row per
-    // lane: bf16 probabilities in B-operand order; returns their sum over this lane's keys.
-    auto exp_tile = [&](const f32x16 &s0, const f32x16 &s1, bf16x8 (&pb)[4], float m_use) -> float {
+    // lane: bf16 probabilities in B-operand order (pb[2b + u] element e is accumulator element
+    // 8u + e of block b); returns their sum over this lane's keys.
+    auto exp_tile = [&](const STile &s, PTile &pb, float m_use) -> float {
         float psum = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-            // pb[ks] element e is accumulator element 8*(ks&1)+e of block ks>>1
-            f32x2 x;
-            bf16x2 y;
-#define CP_EXP_PAIR(SRC, BASE, DST)                                                   \
-            x[0] = fast_exp2(fmaf(SRC[BASE + e], c, -m_use));                         \
-            x[1] = fast_exp2(fmaf(SRC[BASE + e + 1], c, -m_use));                     \
-            y = __builtin_convertvector(x, bf16x2);                                   \
-            psum = __builtin_amdgcn_fdot2_f32_bf16(y, ones, psum, false);             \
-            DST[e] = y[0];                                                            \
-            DST[e + 1] = y[1];
-            CP_EXP_PAIR(s0, 0, pb[0])
-            CP_EXP_PAIR(s0, 8, pb[1])
-            CP_EXP_PAIR(s1, 0, pb[2])
-            CP_EXP_PAIR(s1, 8, pb[3])
-#undef CP_EXP_PAIR
-        }
+        for (int e = 0; e < 8; e += 2)
+#pragma unroll
+            for (int t = 0; t < 2 * kNKB; ++t) {
+                f32x2 x;
+                x[0] = fast_exp2(fmaf(s[t >> 1][8 * (t & 1) + e], c, -m_use));
+                x[1] = fast_exp2(fmaf(s[t >> 1][8 * (t & 1) + e + 1], c, -m_use));
+                const bf16x2 y = __builtin_convertvector(x, bf16x2);
+                psum = __builtin_amdgcn_fdot2_f32_bf16(y, ones, psum, false);
+                pb[t][e] = y[0];
+                pb[t][e + 1] = y[1];
+            }
         return psum;
     };
-    auto row_max = [&](const f32x16 &s0, const f32x16 &s1) -> float {
-        float mx = fmaxf(fmaxf(s0[0], s0[1]), s0[2]);
+    auto row_max = [&](const STile &s) -> float {
+        float mx = s[0][0];
 #pragma unroll
-        for (int v = 3; v < 15; v += 2) mx = fmaxf(fmaxf(mx, s0[v]), s0[v + 1]);
-        mx = fmaxf(fmaxf(mx, s0[15]), s1[0]);
-#pragma unroll
-        for (int v = 1; v < 15; v += 2) mx = fmaxf(fmaxf(mx, s1[v]), s1[v + 1]);
-        mx = fmaxf(mx, s1[15]);
+        for (int i = 1; i + 1 < 16 * kNKB; i += 2) // pairs, so that three-input maxima can be used
+            mx = fmaxf(fmaxf(mx, s[i >> 4][i & 15]), s[(i + 1) >> 4][(i + 1) & 15]);
+        mx = fmaxf(mx, s[kNKB - 1][15]);
         return halfwave_max(mx);
     };
     auto rescale_o = [&](float alpha) {
@@ -347,73 +347,80 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     constexpr float kStale = 1073741824.f; // 2^30
 
     // Classic online-softmax step: row maximum, new reference, rescale of O and l.
-    auto redo_tile = [&](const f32x16 &s0, const f32x16 &s1, bf16x8 (&pb)[4]) -> float {
-        const float m_new = fmaxf(m_ref, row_max(s0, s1) * c);
+    auto redo_tile = [&](const STile &s, PTile &pb) -> float {
+        const float m_new = fmaxf(m_ref, row_max(s) * c);
         const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = fast_exp2(m_ref - m_use);
         rescale_o(alpha);
         l_run *= alpha;
         m_ref = m_new;
-        return exp_tile(s0, s1, pb, m_use);
+        return exp_tile(s, pb, m_use);
     };
     // first key of tile kt in its own numbering (prefix tokens or suffix rows)
     auto tile_key0 = [&](int kt) { return kt >= np_tiles ? (kt - np_tiles) * kBN : kt * kBN; };
-    auto masked_qk = [&](int kt, int buf, f32x16 &s0, f32x16 &s1) {
+    auto masked_qk = [&](int kt, int buf, STile &s) {
         const bool suffix = kt >= np_tiles;
         const int key0 = tile_key0(kt);
-        qk_tile(buf, s0, s1);
+        qk_tile(buf, s);
         const bool need_mask = suffix ? (key0 + kBN - 1 > wave_row0) : (key0 + kBN > P);
-        if (need_mask) mask_tile(suffix ? (row_i - key0 + 1) : (P - key0), s0, s1);
+        if (need_mask) mask_tile(suffix ? (row_i - key0 + 1) : (P - key0), s);
     };
     // a suffix tile entirely above this wavefront's rows shows it nothing, and neither does
     // any later tile
     auto skipped = [&](int kt) { return kt >= np_tiles && tile_key0(kt) > wave_row0 + 31; };
 
-    bf16x8 pb_a[4], pb_b[4]; // probabilities of even / odd tiles
+    PTile pb_a, pb_b; // probabilities of the previous / the current tile
 
     // iteration 0: no previous tile yet, and no reference: classic step
     {
         const bool prefetch = 2 < n_it;
         if (prefetch) load_tile(kt_begin + 2, tr);
         if (!skipped(kt_begin)) {
-            f32x16 s0, s1;
-            masked_qk(kt_begin, 0, s0, s1);
-            l_run += redo_tile(s0, s1, pb_a);
+            STile s;
+            masked_qk(kt_begin, 0, s);
+            l_run += redo_tile(s, pb_a);
             have_prev = true;
         }
         if (prefetch) store_tile(tr, 2);
         __syncthreads();
     }
-    auto tile_step = [&](int it, bf16x8 (&pb_cur)[4], bf16x8 (&pb_prev)[4]) {
+    // One full step; only called for tiles this wavefront does not skip (so the previous tile
+    // was not skipped either and its probabilities are pending).
+    auto tile_step = [&](int it, PTile &pb_cur, PTile &pb_prev) {
         const int buf = it & 3;
         const int kt = kt_begin + it;
         const bool prefetch = it + 2 < n_it;
         if (prefetch) load_tile(kt + 2, tr);
-        if (!skipped(kt)) {
-            // the previous tile was not skipped either, so its probabilities are pending
-            f32x16 s0, s1;
-            masked_qk(kt, buf, s0, s1);
-            // one basic block: the exponentials (VALU) interleave with P V (MFMA)
-            float psum = exp_tile(s0, s1, pb_cur, (m_ref == -INFINITY) ? 0.f : m_ref);
-            pv_tile((buf + 3) & 3, pb_prev);
-            if (__builtin_amdgcn_ballot_w64(!(psum < kStale) || m_ref == -INFINITY) != 0)
-                psum = redo_tile(s0, s1, pb_cur);
-            l_run += psum;
-        } else if (have_prev) {
-            pv_tile((buf + 3) & 3, pb_prev);
-            have_prev = false;
-        }
+        STile s;
+        masked_qk(kt, buf, s);
+        // one basic block: the exponentials (VALU) interleave with P V (MFMA)
+        float psum = exp_tile(s, pb_cur, (m_ref == -INFINITY) ? 0.f : m_ref);
+        pv_tile((buf + 3) & 3, pb_prev);
+        if (__builtin_amdgcn_ballot_w64(!(psum < kStale) || m_ref == -INFINITY) != 0)
+            psum = redo_tile(s, pb_cur);
+        l_run += psum;
         if (prefetch) store_tile(tr, (buf + 2) & 3);
         __syncthreads();
     };
-    for (int it = 1; it < n_it; it += 2) {
-        tile_step(it, pb_b, pb_a);
-        if (it + 1 < n_it) tile_step(it + 1, pb_a, pb_b);
-    }
-    // P V of the last tile (a wavefront that skipped tiles has already done it)
+    int it = 1;
     if (have_prev) {
-        if ((n_it - 1) & 1) pv_tile((n_it - 1) & 3, pb_b);
-        else pv_tile((n_it - 1) & 3, pb_a);
+        // a single call site, so that the accumulators stay in the same registers throughout
+        for (; it < n_it && !skipped(kt_begin + it); ++it) {
+            tile_step(it, pb_b, pb_a);
+#pragma unroll
+            for (int t = 0; t < 2 * kNKB; ++t) pb_a[t] = pb_b[t];
+        }
+        // P V of the last tile this wavefront computed (tile it - 1)
+        pv_tile((it - 1) & 3, pb_a);
+    }
+    // remaining tiles are invisible to this wavefront: only take part in the cooperative loads
+    for (; it < n_it; ++it) {
+        const bool prefetch = it + 2 < n_it;
+        if (prefetch) {
+            load_tile(kt_begin + it + 2, tr);
+            store_tile(tr, (it + 2) & 3);
+        }
+        __syncthreads();
     }
 
     // ---- epilogue.  o[db][v] is O^T[d = db*32 + 8*(v/4) + 4*h + v%4][row j]
