@@ -57,7 +57,7 @@ struct AttnParams {
     float *part_ml; // [nsplit][T][Hq][2]   running max (log2 domain) and sum
     int32_t batch, Hq, Hkv, G, max_pages, T;
     int32_t nsplit;
-    int32_t items_per_head; // q tiles * G * nsplit
+    int32_t items_per_head; // work units per KV head * nsplit
     int32_t total_items;    // items_per_head * Hkv
     int32_t items_per_xcd;  // ceil(total_items / 8)
     float scale_log2;       // softmax_scale * log2(e)
@@ -75,6 +75,16 @@ __device__ __forceinline__ float halfwave_sum(float x)
 {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Number of q heads of one KV head that share a workgroup (GQA head sharing): short extends
+// leave most of a 256-row tile empty, so the rows of up to 8 heads are packed into it.  The
+// largest power of two that divides G and still gives every head enough rows for E.
+__host__ __device__ inline int heads_per_tile(int E, int G)
+{
+    int pack = 1;
+    while (pack < 8 && G % (pack * 2) == 0 && E * (pack * 2) <= kBM) pack *= 2;
+    return pack;
 }
 
 // K/V tile of 64 keys: each of the 512 threads stages two 16-byte chunks of K and two of V in
@@ -121,30 +131,35 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     const int kvh = vid / p.items_per_head;
     int rem = vid - kvh * p.items_per_head;
     const int split = rem % p.nsplit;
-    rem /= p.nsplit;
-    const int g = rem % p.G;
-    int qt_rank = rem / p.G;
-    const int head = kvh * p.G + g;
+    int unit = rem / p.nsplit;
 
-    // requests in order; within a request the last (longest) q tile first
-    int r = 0, cu = 0, E = 0, t = 0;
+    // Units of a KV head: requests in order; within a request the last (longest) row tile
+    // first, and for each row tile the groups of q heads that are packed into one workgroup.
+    int r = 0, cu = 0, E = 0, t = 0, pack = 1, hgroup = 0;
     for (; r < p.batch; ++r) {
         E = p.extend_lens[r];
-        const int nt = (E + kBM - 1) / kBM;
-        if (qt_rank < nt) {
-            t = nt - 1 - qt_rank;
+        pack = heads_per_tile(E, p.G);
+        const int groups = p.G / pack;
+        const int nt = (E * pack + kBM - 1) / kBM; // row tiles of kBM / pack rows
+        if (unit < nt * groups) {
+            hgroup = unit % groups;
+            t = nt - 1 - unit / groups;
             break;
         }
-        qt_rank -= nt;
+        unit -= nt * groups;
         cu += E;
     }
     if (r >= p.batch) return;
     const int P = p.prefix_lens[r];
 
-    const int q0 = t * kBM;                          // first extend row of the workgroup
-    const int wave_row0 = q0 + wave * 32;            // first extend row of this wavefront
-    const int row_i = wave_row0 + j;                 // this lane's extend row (may be >= E)
-    const int rows_end = min(E, q0 + kBM);           // one past the last valid row of the tile
+    // GQA head sharing: `pack` q heads of the KV head share the workgroup's K/V tiles, each
+    // with kBM / pack query rows; a wavefront belongs to exactly one of them.
+    const int rows_per_head = kBM / pack;
+    const int head = kvh * p.G + hgroup * pack + (wave * 32) / rows_per_head;
+    const int q0 = t * rows_per_head;                          // first extend row of the tile
+    const int wave_row0 = q0 + (wave * 32) % rows_per_head;    // first row of this wavefront
+    const int row_i = wave_row0 + j;                           // this lane's extend row (may be >= E)
+    const int rows_end = min(E, q0 + rows_per_head);           // one past the last valid row
     const int np_tiles = (P + kBN - 1) / kBN;        // prefix key tiles
     const int ns_tiles = (rows_end + kBN - 1) / kBN; // suffix key tiles up to the diagonal
     const int n_tiles = np_tiles + ns_tiles;
@@ -533,7 +548,7 @@ __global__ __launch_bounds__(256) void write_kv_kernel(const uint16_t *__restric
 
 // ------------------------------------------------------------------ host side
 struct Plan {
-    int64_t q_tiles;   // sum_r ceil(E_r / kBM)
+    int64_t q_tiles;   // work units per KV head: row tiles x head groups, summed over requests
     int32_t max_key_tiles;
     int32_t nsplit;
 };
@@ -593,7 +608,8 @@ Plan make_plan(const cp_shape *s)
     for (int r = 0; r < s->batch; ++r) {
         const int64_t P = s->h_prefix_lens[r], E = s->h_extend_lens[r];
         if (E == 0) continue;
-        pl.q_tiles += (E + kBM - 1) / kBM;
+        const int pack = heads_per_tile((int)E, s->num_q_heads / s->num_kv_heads);
+        pl.q_tiles += ((E * pack + kBM - 1) / kBM) * (s->num_q_heads / s->num_kv_heads / pack);
         const int64_t kt = (P + kBN - 1) / kBN + (E + kBN - 1) / kBN;
         if (kt > pl.max_key_tiles) pl.max_key_tiles = (int32_t)kt;
     }
@@ -602,7 +618,7 @@ Plan make_plan(const cp_shape *s)
     } else {
         // Split the keys only when the unsplit grid cannot give every CU two workgroups, and
         // never into pieces shorter than 8 key tiles.
-        const int64_t items = pl.q_tiles * s->num_q_heads;
+        const int64_t items = pl.q_tiles * s->num_kv_heads;
         const int64_t want = 2LL * num_cus();
         int64_t ns = 1;
         if (items > 0 && items < want) ns = (want + items - 1) / items;
@@ -668,7 +684,7 @@ int cp_extend_attention(const void *q, const void *k_new, const void *v_new, con
         if (!workspace || workspace_bytes < need) return CP_ERR_WORKSPACE;
         if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return CP_ERR_WORKSPACE;
     }
-    const int64_t per_head = pl.q_tiles * (shape->num_q_heads / shape->num_kv_heads) * pl.nsplit;
+    const int64_t per_head = pl.q_tiles * pl.nsplit;
     const int64_t total = per_head * shape->num_kv_heads;
     if (total > INT32_MAX / 2) return CP_ERR_SHAPE;
 

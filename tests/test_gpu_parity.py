@@ -56,6 +56,18 @@ def test_gqa_group_sizes(H, G, Hkv):
     _check(H.gpu_attention(w), oracle.attention_of(w), f"G={G} Hkv={Hkv}")
 
 
+@pytest.mark.parametrize("G,Hkv,E", [
+    (4, 2, [1, 17, 32]), (4, 2, [33, 64, 100]), (4, 2, [128, 129, 5]),
+    (8, 1, [1, 31, 40]), (8, 1, [64, 65, 256]), (6, 1, [20, 70, 130]), (2, 3, [127, 3, 257]),
+])
+def test_short_extends_pack_several_heads_per_workgroup(H, G, Hkv, E):
+    """Short extends share one workgroup's K/V tiles between q heads of a KV head."""
+    w = W.make_uniform("pack", 111, len(E), G * Hkv, Hkv, [300, 0, 77], E)
+    want = oracle.attention_of(w)
+    _check(H.gpu_attention(w), want, f"pack G={G} E={E}")
+    _check(H.gpu_attention(w, num_splits=3), want, f"pack split G={G} E={E}")
+
+
 @pytest.mark.parametrize("ns", [2, 3, 7, 64])
 def test_forced_split_k_matches_and_is_deterministic(H, ns):
     w = W.make_uniform("split", 103, 2, 4, 2, [1000, 37], [300, 150])
