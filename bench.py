@@ -24,6 +24,26 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
+# HBM bytes per launch of extend_attn_kernel from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0 +
+# WRITE_SIZE x 1.0, scale factors from a 1 GiB device copy in the same run), valid only for the
+# kernel source they were taken with: reported as null as soon as that source changes.
+TRAFFIC = {
+    "source_sha256_16": "080215f6623107fd",
+    "long_context_32k": (2130217 * 2.0 + 524290) * 1024.0,
+}
+
+
+def measured_traffic(workload: str):
+    import hashlib
+    src = os.path.join(ROOT, "paper_2511_03475_amd", "csrc", "cp_extend.hip")
+    try:
+        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+    if digest != TRAFFIC["source_sha256_16"]:
+        return None
+    return TRAFFIC.get(workload)
+
 
 def _workload(name: str):
     import workloads as W
@@ -220,7 +240,7 @@ def main():
                    "step": "cp_write_kv + cp_extend_attention", "splits": head["splits"]},
         "roofline": {"bound": "mfma", "kernel": "extend_attn_kernel",
                      "achieved": head["tflops_attn"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": head["frac_mfma_peak"], "traffic": None,
+                     "frac": head["frac_mfma_peak"], "traffic": measured_traffic(args.workload),
                      "avg_kernel_ms": head["attn_ms_avg"]},
         "cpu_baseline": cpu,
     }
