@@ -1,0 +1,99 @@
+"""The C-ABI library loads, exports every function the header declares, and its host-side
+argument checks and launch planning work without a GPU (no kernel is launched here)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2511_03475_amd as cp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(cp.LIB_PATH):
+        cp.build()
+    return cp.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "cp_extend.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cp_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert set(names) == set(cp.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(lib):
+    assert cp.cp_status_string(cp.CP_OK) == "ok"
+    for code in (cp.CP_ERR_NULL, cp.CP_ERR_SHAPE, cp.CP_ERR_WORKSPACE, cp.CP_ERR_LAUNCH, -99):
+        assert len(cp.cp_status_string(code)) > 3
+
+
+def _shape(P, E, Hq=32, Hkv=8, splits=0, D=128, PS=16, pages=None, width=None):
+    need = max((p + e + 15) // 16 for p, e in zip(P, E))
+    return cp.Shape(len(P), Hq, Hkv, D, PS, pages or 100000, width or max(need, 1), P, E,
+                    1.0 / np.sqrt(128), num_splits=splits)
+
+
+def test_split_plan_is_a_pure_function_of_the_shape(lib):
+    big = _shape([24576] * 4, [8192] * 4, Hq=64)
+    assert cp.cp_num_splits(big) == 1 and cp.cp_workspace_bytes(big) == 0
+    forced = _shape([24576] * 4, [8192] * 4, Hq=64, splits=2)
+    assert cp.cp_num_splits(forced) == 2
+    rows = 2 * 4 * 8192 * 64
+    assert cp.cp_workspace_bytes(forced) == rows * 128 * 4 + rows * 2 * 4
+    short = _shape([10240], [128])           # one short request: few workgroups -> split
+    ns = cp.cp_num_splits(short)
+    assert 1 < ns <= 64 and cp.cp_workspace_bytes(short) > 0
+    assert cp.cp_num_splits(_shape([10240], [128])) == ns
+
+
+def test_invalid_shapes_are_rejected_on_the_host(lib):
+    bad = [
+        _shape([32], [32], Hq=4, Hkv=3),           # Hq % Hkv != 0
+        _shape([32], [32], D=64),                  # head_dim
+        _shape([32], [32], PS=32),                 # page_size
+        _shape([32], [32], width=1),               # table too narrow
+        _shape([-1], [32], width=4),               # negative length
+        _shape([32], [32], splits=65),             # split factor out of range
+    ]
+    for sh in bad:
+        assert cp.cp_num_splits(sh) == 0 and cp.cp_workspace_bytes(sh) == 0
+        st = cp.cp_extend_attention(1, 1, 1, 1, 1, 1, 1, 1, None, sh, None, 0, check=False)
+        assert st == cp.CP_ERR_SHAPE
+        st = cp.cp_write_kv(1, 1, 1, 1, 1, 1, None, sh, check=False)
+        assert st == cp.CP_ERR_SHAPE
+    wrong_total = cp.Shape(1, 4, 2, 128, 16, 64, 8, [32], [32], 0.1, total_extend=31)
+    assert cp.cp_extend_attention(1, 1, 1, 1, 1, 1, 1, 1, None, wrong_total, None, 0,
+                                  check=False) == cp.CP_ERR_SHAPE
+
+
+def test_null_pointers_and_missing_workspace_are_rejected_before_any_launch(lib):
+    ok = _shape([32], [32], Hq=4, Hkv=2, splits=2)
+    assert cp.cp_extend_attention(None, 1, 1, 1, 1, 1, 1, 1, None, ok, None, 0,
+                                  check=False) == cp.CP_ERR_NULL
+    assert cp.cp_extend_attention(1, 1, 1, 1, None, 1, 1, 1, None, ok, None, 0,
+                                  check=False) == cp.CP_ERR_NULL
+    assert cp.cp_extend_attention(256, 256, 256, 256, 256, 256, 256, 256, None, ok, None, 0,
+                                  check=False) == cp.CP_ERR_WORKSPACE
+    assert cp.cp_extend_attention(256, 256, 256, 256, 256, 256, 256, 256, None, ok, 128, 1 << 30,
+                                  check=False) == cp.CP_ERR_WORKSPACE      # misaligned
+    assert cp.cp_write_kv(None, 1, 1, 1, 1, 1, None, ok, check=False) == cp.CP_ERR_NULL
+    with pytest.raises(cp.CpError):
+        cp.cp_write_kv(None, 1, 1, 1, 1, 1, None, ok)
+
+
+def test_empty_batch_is_a_no_op(lib):
+    sh = _shape([16, 0], [0, 0], Hq=4, Hkv=2)
+    assert cp.cp_extend_attention(None, None, None, None, 1, 1, 1, None, None, sh, None, 0,
+                                  check=False) == cp.CP_OK
+    assert cp.cp_write_kv(None, None, None, 1, 1, 1, None, sh, check=False) == cp.CP_OK
