@@ -14,16 +14,18 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "extend_attention_oracle.c")
+_SRCS = [os.path.join(_HERE, "extend_attention_oracle.c"),
+         os.path.join(_HERE, "context_distance_oracle.c")]
 _LIB = os.path.join(_HERE, "libcp_oracle.so")
 _lib = None
 
 
 def build(force: bool = True) -> str:
     """Compile the oracle with gcc (plain C + OpenMP)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_LIB) or \
+            os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS):
         cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-               _SRC, "-o", _LIB, "-lm"]
+               *_SRCS, "-o", _LIB, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -46,6 +48,9 @@ def _load():
         lib.oracle_write_kv.argtypes = [
             u16p, u16p, u16p, i32p, i32p, i32p,
             ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+        lib.oracle_context_distance.restype = ctypes.c_int
+        lib.oracle_context_distance.argtypes = [i32p, i32p, ctypes.c_int32, ctypes.c_int32,
+                                                ctypes.c_double, f64p]
         _lib = lib
     return _lib
 
@@ -126,3 +131,22 @@ def attention_of(w, rows=None, **kw):
     """Oracle attention on a workloads.Workload-shaped object (duck-typed fields)."""
     return extend_attention(w.q, w.k_new, w.v_new, w.kv_pages, w.block_table, w.prefix_lens,
                             w.extend_lens, w.softmax_scale, rows=rows, **kw)
+
+
+def context_distance(contexts, lens, alpha: float) -> np.ndarray:
+    """Pairwise context distance (paper, Eq. 1) in fp64.
+
+    contexts [n, stride] int32 (row i holds lens[i] distinct block ids in rank order),
+    lens [n] int32.  Returns dist [n, n] float64.
+    """
+    lib = _load()
+    contexts, cp_ = _i32(contexts)
+    lens, lp = _i32(lens)
+    n, stride = contexts.shape
+    assert lens.shape == (n,)
+    out = np.zeros((n, n), dtype=np.float64)
+    rc = lib.oracle_context_distance(cp_, lp, n, stride, float(alpha),
+                                     out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    if rc != 0:
+        raise ValueError("oracle_context_distance rejected its arguments")
+    return out

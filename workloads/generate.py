@@ -302,3 +302,36 @@ def sample_rows(w: Workload, seed: int, q_block: int = 128, edge: int = 16,
     if not rows:
         return np.zeros(0, dtype=np.int32)
     return np.unique(np.concatenate(rows)).astype(np.int32)
+
+
+def make_contexts(seed: int, n: int, k, pool_ids: int = 2000, zipf_s: float = 1.1,
+                  stride: Optional[int] = None):
+    """Contexts for the context index (paper, Section 4.1): n ordered lists of distinct block ids.
+
+    Each context draws its ids without replacement with weight rank^-s (heavy-tailed block
+    popularity); the draw order stands for the retriever's relevance order.  k is the number of
+    blocks per context (an int, or a (lo, hi) range drawn uniformly per context).
+    Returns (contexts [n, stride] int32 padded with -1, lens [n] int32).
+    """
+    rng = np.random.default_rng(seed)
+    if isinstance(k, int):
+        lens = np.full(n, k, dtype=np.int32)
+    else:
+        lens = rng.integers(k[0], k[1] + 1, size=n).astype(np.int32)
+    kmax = int(lens.max()) if n else 0
+    stride = stride or max(kmax, 1)
+    assert stride >= kmax and pool_ids >= kmax
+    w = (np.arange(pool_ids, dtype=np.float64) + 1.0) ** (-zipf_s)
+    # Gumbel top-k: the kmax largest perturbed log-weights, in order, are a draw without
+    # replacement with probabilities proportional to w
+    contexts = np.full((n, stride), -1, dtype=np.int32)
+    logw = np.log(w)
+    chunk = 4096
+    for lo in range(0, n, chunk):
+        hi = min(lo + chunk, n)
+        g = logw[None, :] + rng.gumbel(size=(hi - lo, pool_ids))
+        top = np.argsort(-g, axis=1)[:, :kmax].astype(np.int32)
+        contexts[lo:hi, :kmax] = top
+    for i in range(n):
+        contexts[i, lens[i]:] = -1
+    return contexts, lens
