@@ -173,6 +173,48 @@ def cpu_baseline(w, budget_s: float = 15.0):
                       f"{w.flops() / (fl / dt):.0f} s"}
 
 
+PEAK_INT32_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, one 32-bit op per lane
+
+
+def measure_context_distance(n: int = 8192, k: int = 15, stride: int = 16, steps: int = 20,
+                             cpu: bool = True):
+    """Pairwise context distance (paper, Eq. 1) for the index build: n contexts x top-k ids."""
+    import torch
+    import paper_2511_03475_amd as cp
+    import workloads as W
+    C, L = W.make_contexts(20251110, n, k, pool_ids=2000, stride=stride)
+    dc, dl = torch.from_numpy(C).to("cuda:0"), torch.from_numpy(L).to("cuda:0")
+    out = torch.empty((n, n), dtype=torch.float32, device="cuda:0")
+    stream = torch.cuda.current_stream()
+    for _ in range(3):
+        cp.cp_context_distance(dc, dl, n, stride, 0.001, out, stream)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    ev[0].record(stream)
+    for i in range(steps):
+        cp.cp_context_distance(dc, dl, n, stride, 0.001, out, stream)
+        ev[i + 1].record(stream)
+    torch.cuda.synchronize()
+    ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]))
+    # the kernel does one compare and one conditional move per pair of (padded) positions
+    ops = 2.0 * n * n * stride * stride
+    res = {"workload": f"context_distance n={n} k={k}", "ms": ms, "pairs_per_s": n * n / (ms * 1e-3),
+           "roofline": {"bound": "alu", "achieved": ops / (ms * 1e-3) / 1e12, "peak": PEAK_INT32_TOPS,
+                        "unit": "Tops/s (int32)", "frac": ops / (ms * 1e-3) / 1e12 / PEAK_INT32_TOPS,
+                        "traffic": None},
+           "write_gbs": n * n * 4 / (ms * 1e-3) / 1e9}
+    if cpu:
+        import oracle
+        m = n
+        t = time.perf_counter()
+        oracle.context_distance(C[:m], L[:m], 0.001)
+        dt = time.perf_counter() - t
+        res["cpu_baseline"] = {"value": m * m / dt, "unit": "pairs/s", "kind": "oracle",
+                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
+                               "sample": f"all {m} contexts ({m * m} pairs), {dt:.2f} s of fp64 oracle"}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -252,6 +294,8 @@ def main():
             line["rag_zipf_hit_ratio"] = zipf.get("token_hit_ratio")
     if reuse:
         line["reuse_speedup_128k"] = reuse
+    if not args.no_extra:
+        line["context_distance"] = measure_context_distance(cpu=not args.no_cpu)
     print(json.dumps(line))
 
 

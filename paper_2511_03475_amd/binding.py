@@ -22,7 +22,7 @@ CP_ERR_WORKSPACE = -3
 CP_ERR_LAUNCH = -4
 
 EXPORTS = ("cp_workspace_bytes", "cp_num_splits", "cp_extend_attention", "cp_write_kv",
-           "cp_status_string")
+           "cp_status_string", "cp_context_distance")
 
 
 class cp_shape(ctypes.Structure):
@@ -63,6 +63,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.cp_extend_attention.argtypes = [vp, vp, vp, vp, i32p, i32p, i32p, vp, vp, sp, vp, ctypes.c_size_t]
     lib.cp_write_kv.restype = ctypes.c_int
     lib.cp_write_kv.argtypes = [vp, vp, vp, i32p, i32p, i32p, vp, sp]
+    lib.cp_context_distance.restype = ctypes.c_int
+    lib.cp_context_distance.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_float, vp, vp]
     lib.cp_status_string.restype = ctypes.c_char_p
     lib.cp_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -136,4 +138,13 @@ def cp_write_kv(k_new, v_new, kv_pages, block_table, prefix_lens, extend_lens, s
         _ptr(extend_lens), _stream(stream), shape.ref())
     if check and st != CP_OK:
         raise CpError(st, "cp_write_kv")
+    return st
+
+
+def cp_context_distance(contexts, lens, n: int, stride: int, alpha: float, dist, stream,
+                        check: bool = True) -> int:
+    st = load_library().cp_context_distance(_ptr(contexts), _ptr(lens), int(n), int(stride),
+                                            float(alpha), _ptr(dist), _stream(stream))
+    if check and st != CP_OK:
+        raise CpError(st, "cp_context_distance")
     return st

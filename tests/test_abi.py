@@ -20,9 +20,13 @@ def lib():
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "cp_extend.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(cp_[a-z_]+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for f in sorted(os.listdir(inc)):
+        if f.endswith(".h"):
+            text = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, f)).read(), flags=re.S)
+            names |= set(re.findall(r"\b(cp_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -97,3 +101,14 @@ def test_empty_batch_is_a_no_op(lib):
     assert cp.cp_extend_attention(None, None, None, None, 1, 1, 1, None, None, sh, None, 0,
                                   check=False) == cp.CP_OK
     assert cp.cp_write_kv(None, None, None, 1, 1, 1, None, sh, check=False) == cp.CP_OK
+
+
+def test_context_distance_argument_checks(lib):
+    f = cp.cp_context_distance
+    assert f(1, 1, -1, 16, 0.001, 1, None, check=False) == -2
+    assert f(1, 1, 10, 0, 0.001, 1, None, check=False) == -2
+    assert f(1, 1, 10, 33, 0.001, 1, None, check=False) == -2
+    assert f(1, 1, 10, 6, 0.001, 1, None, check=False) == -2            # stride not a multiple of 4
+    assert f(1, 1, 10, 16, -1.0, 1, None, check=False) == -2
+    assert f(None, 1, 10, 16, 0.001, 1, None, check=False) == -1
+    assert f(None, None, 0, 16, 0.001, None, None, check=False) == 0     # nothing to do
