@@ -51,6 +51,12 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     if _lib is not None and path is None:
         return _lib
     path = path or LIB_PATH
+    # PyTorch ships its own copy of the HIP runtime; if this library were loaded first it
+    # would bring in the system copy, and the two runtimes do not share devices or streams.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.path.exists(path):
         raise RuntimeError(f"{path} is missing: build it first (python -m paper_2511_03475_amd.build)")
     lib = ctypes.CDLL(path)
