@@ -215,6 +215,26 @@ def measure_context_distance(n: int = 8192, k: int = 15, stride: int = 16, steps
     return res
 
 
+def measure_mfma_ceiling(iters: int = 100000):
+    """What the matrix pipe of this device sustains on nothing but back-to-back MFMAs, with
+    constant operands and with random-looking ones (the rate depends on operand bit toggling)."""
+    import torch
+    import paper_2511_03475_amd as cp
+    sink = torch.empty(cp.cp_probe_mfma_sink_floats(), dtype=torch.float32, device="cuda:0")
+    stream = torch.cuda.current_stream()
+    out = {}
+    for name, rnd in (("constant_operands", False), ("random_operands", True)):
+        cp.cp_probe_mfma(rnd, 1000, sink, stream)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record(stream)
+        cp.cp_probe_mfma(rnd, iters, sink, stream)
+        b.record(stream)
+        torch.cuda.synchronize()
+        out[name] = cp.cp_probe_mfma_flops(iters) / (a.elapsed_time(b) * 1e-3) / 1e12
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -296,6 +316,9 @@ def main():
         line["reuse_speedup_128k"] = reuse
     if not args.no_extra:
         line["context_distance"] = measure_context_distance(cpu=not args.no_cpu)
+        ceil = measure_mfma_ceiling()
+        line["roofline"]["measured_mfma_ceiling_tflops"] = ceil
+        line["roofline"]["frac_of_measured_ceiling"] = head["tflops_attn"] / ceil["random_operands"]
     print(json.dumps(line))
 
 

@@ -2,6 +2,6 @@
 from .binding import (  # noqa: F401
     CP_ERR_LAUNCH, CP_ERR_NULL, CP_ERR_SHAPE, CP_ERR_WORKSPACE, CP_OK, EXPORTS, CpError, Shape,
     cp_context_distance, cp_extend_attention, cp_num_splits, cp_shape, cp_status_string, cp_workspace_bytes,
-    cp_write_kv, load_library,
+    cp_probe_mfma, cp_probe_mfma_flops, cp_probe_mfma_sink_floats, cp_write_kv, load_library,
 )
 from .build import LIB_PATH, build  # noqa: F401

@@ -22,7 +22,8 @@ CP_ERR_WORKSPACE = -3
 CP_ERR_LAUNCH = -4
 
 EXPORTS = ("cp_workspace_bytes", "cp_num_splits", "cp_extend_attention", "cp_write_kv",
-           "cp_status_string", "cp_context_distance")
+           "cp_status_string", "cp_context_distance", "cp_probe_mfma",
+           "cp_probe_mfma_sink_floats", "cp_probe_mfma_flops")
 
 
 class cp_shape(ctypes.Structure):
@@ -71,6 +72,12 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.cp_write_kv.argtypes = [vp, vp, vp, i32p, i32p, i32p, vp, sp]
     lib.cp_context_distance.restype = ctypes.c_int
     lib.cp_context_distance.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_float, vp, vp]
+    lib.cp_probe_mfma.restype = ctypes.c_int
+    lib.cp_probe_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
+    lib.cp_probe_mfma_sink_floats.restype = ctypes.c_size_t
+    lib.cp_probe_mfma_sink_floats.argtypes = []
+    lib.cp_probe_mfma_flops.restype = ctypes.c_double
+    lib.cp_probe_mfma_flops.argtypes = [ctypes.c_int32]
     lib.cp_status_string.restype = ctypes.c_char_p
     lib.cp_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -154,3 +161,18 @@ def cp_context_distance(contexts, lens, n: int, stride: int, alpha: float, dist,
     if check and st != CP_OK:
         raise CpError(st, "cp_context_distance")
     return st
+
+
+def cp_probe_mfma(random_operands: bool, iters: int, sink, stream, check: bool = True) -> int:
+    st = load_library().cp_probe_mfma(int(bool(random_operands)), int(iters), _ptr(sink), _stream(stream))
+    if check and st != CP_OK:
+        raise CpError(st, "cp_probe_mfma")
+    return st
+
+
+def cp_probe_mfma_sink_floats() -> int:
+    return int(load_library().cp_probe_mfma_sink_floats())
+
+
+def cp_probe_mfma_flops(iters: int) -> float:
+    return float(load_library().cp_probe_mfma_flops(int(iters)))
