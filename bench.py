@@ -55,8 +55,36 @@ def _workload(name: str):
         "ctx128k_zero_reuse": lambda: W.config5_128k(False),
         "ctx128k_reuse": lambda: W.config5_128k(True),
         "short_extend_probe": W.probe_short_extend,
+        "rag_zipf_context_index": rag_zipf_context_index,
+        "rag_zipf_as_retrieved": lambda: W.rag_batch_from_blocks("rag_zipf_as_retrieved", W.BASE_SEED + 3,
+                                                                 W.rag_zipf_picks()),
     }
     return table[name]()
+
+
+def index_align(picks, alpha: float = 0.001):
+    """Aligned block orders and execution order of a batch from the context index library
+    (construction, alignment and scheduling of the paper, Sections 4-5)."""
+    import paper_2511_03475_amd as cp
+    stride = max(len(p) for p in picks)
+    C = np.full((len(picks), stride), -1, np.int32)
+    L = np.zeros(len(picks), np.int32)
+    for i, p in enumerate(picks):
+        C[i, :len(p)] = p
+        L[i] = len(p)
+    idx = cp.ContextIndex(C, L, alpha)
+    aligned = [idx.aligned(i) for i in range(len(picks))]
+    order = cp.cp_index_schedule([idx.path(i) for i in range(len(picks))])
+    idx.close()
+    return aligned, order
+
+
+def rag_zipf_context_index():
+    """The rag_zipf batch (same retrieved blocks) with the block order and the execution order
+    chosen by the context index instead of the frequency sort."""
+    import workloads as W
+    aligned, order = index_align(W.rag_zipf_picks())
+    return W.rag_batch_from_blocks("rag_zipf_context_index", W.BASE_SEED + 3, aligned, order=order)
 
 
 def algorithmic_bytes(w) -> float:
@@ -215,6 +243,47 @@ def measure_context_distance(n: int = 8192, k: int = 15, stride: int = 16, steps
     return res
 
 
+def measure_context_index(n: int = 2000, k: int = 15, cpu: bool = True):
+    """Index construction for n contexts of k retrieved blocks: Eq. 1 distances on the GPU,
+    clustering / tree / alignment / schedule in the host library."""
+    import torch
+    import paper_2511_03475_amd as cp
+    import workloads as W
+    stride = 16
+    C, L = W.make_contexts(20251111, n, k, pool_ids=2000, stride=stride)
+    t0 = time.perf_counter()
+    first_of, m = cp.cp_index_distinct(C, L)
+    rows = np.zeros(m, np.int64)
+    rows[first_of[::-1]] = np.arange(n)[::-1]            # first row of every distinct context
+    dc, dl = torch.from_numpy(C[rows]).to("cuda:0"), torch.from_numpy(L[rows]).to("cuda:0")
+    out = torch.empty((m, m), dtype=torch.float32, device="cuda:0")
+    cp.cp_context_distance(dc, dl, m, stride, 0.001, out, torch.cuda.current_stream())
+    D = out.cpu().numpy()
+    t1 = time.perf_counter()
+    idx = cp.ContextIndex(C, L, 0.001, dist=D)
+    t2 = time.perf_counter()
+    paths = [idx.path(i) for i in range(n)]
+    order = cp.cp_index_schedule(paths)
+    t3 = time.perf_counter()
+    res = {"workload": f"context_index n={n} k={k}", "distinct": m, "nodes": idx.num_nodes(),
+           "distance_gpu_incl_copies_s": t1 - t0, "cluster_tree_align_s": t2 - t1,
+           "paths_schedule_s": t3 - t2, "total_s": t3 - t0, "contexts_per_s": n / (t3 - t0)}
+    idx.close()
+    assert sorted(order) == list(range(n))
+    if cpu:
+        from oracle import context_index as CI
+        ns = 300
+        sample = [list(map(int, C[i, :L[i]])) for i in range(ns)]
+        t = time.perf_counter()
+        ref = CI.ContextIndex.build(sample, 0.001)
+        CI.schedule([ref.path(i) for i in range(ns)])
+        dt = time.perf_counter() - t
+        res["cpu_baseline"] = {"value": ns / dt, "unit": "contexts/s", "kind": "oracle", "cores": 1,
+                               "sample": f"first {ns} of {n} contexts (cubic-time reference, {dt:.1f} s); "
+                                         "not comparable at equal n"}
+    return res
+
+
 def measure_mfma_ceiling(iters: int = 100000):
     """What the matrix pipe of this device sustains on nothing but back-to-back MFMAs, with
     constant operands and with random-looking ones (the rate depends on operand bit toggling)."""
@@ -273,12 +342,12 @@ def main():
 
     extra = []
     if not args.no_extra:
-        for name in ("tiny_extend", "rag_fixed", "rag_zipf", "long_context_32k",
-                     "ctx128k_zero_reuse", "ctx128k_reuse", "short_extend_probe"):
+        for name in ("tiny_extend", "rag_fixed", "rag_zipf", "rag_zipf_as_retrieved", "rag_zipf_context_index",
+                     "long_context_32k", "ctx128k_zero_reuse", "ctx128k_reuse", "short_extend_probe"):
             if name == args.workload:
                 extra.append({k: head[k] for k in head})
                 continue
-            steps = 5 if name.startswith("ctx128k") or name == "rag_zipf" else 20
+            steps = 5 if name.startswith("ctx128k") or name.startswith("rag_zipf") else 20
             _, rr, res = measure(name, steps, 2)
             extra.append(res)
             del rr
@@ -309,13 +378,14 @@ def main():
     if extra:
         line["workloads"] = [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in e.items()
                               if k not in ("notes",)} for e in extra]
-        zipf = by.get("rag_zipf", {}).get("notes")
-        if zipf:
-            line["rag_zipf_hit_ratio"] = zipf.get("token_hit_ratio")
+        line["rag_zipf_hit_ratio"] = {name: by[name]["notes"]["token_hit_ratio"]
+                                      for name in ("rag_zipf_as_retrieved", "rag_zipf", "rag_zipf_context_index")
+                                      if name in by and "notes" in by[name]}
     if reuse:
         line["reuse_speedup_128k"] = reuse
     if not args.no_extra:
         line["context_distance"] = measure_context_distance(cpu=not args.no_cpu)
+        line["context_index"] = measure_context_index(cpu=not args.no_cpu)
         ceil = measure_mfma_ceiling()
         line["roofline"]["measured_mfma_ceiling_tflops"] = ceil
         line["roofline"]["frac_of_measured_ceiling"] = head["tflops_attn"] / ceil["random_operands"]

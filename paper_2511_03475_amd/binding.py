@@ -23,7 +23,10 @@ CP_ERR_LAUNCH = -4
 
 EXPORTS = ("cp_workspace_bytes", "cp_num_splits", "cp_extend_attention", "cp_write_kv",
            "cp_status_string", "cp_context_distance", "cp_probe_mfma",
-           "cp_probe_mfma_sink_floats", "cp_probe_mfma_flops")
+           "cp_probe_mfma_sink_floats", "cp_probe_mfma_flops",
+           "cp_index_distinct", "cp_index_build", "cp_index_free", "cp_index_num_contexts",
+           "cp_index_num_nodes", "cp_index_aligned", "cp_index_path", "cp_index_leaf", "cp_index_node",
+           "cp_index_children", "cp_index_search", "cp_index_insert", "cp_index_schedule")
 
 
 class cp_shape(ctypes.Structure):
@@ -78,6 +81,34 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.cp_probe_mfma_sink_floats.argtypes = []
     lib.cp_probe_mfma_flops.restype = ctypes.c_double
     lib.cp_probe_mfma_flops.argtypes = [ctypes.c_int32]
+    i32, i32p, f64p = ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double)
+    lib.cp_index_distinct.restype = ctypes.c_int
+    lib.cp_index_distinct.argtypes = [i32p, i32p, i32, i32, i32p, i32p]
+    lib.cp_index_build.restype = ctypes.c_int
+    lib.cp_index_build.argtypes = [i32p, i32p, i32, i32, ctypes.c_double, ctypes.POINTER(ctypes.c_float), i32,
+                                   ctypes.POINTER(vp)]
+    lib.cp_index_free.restype = None
+    lib.cp_index_free.argtypes = [vp]
+    lib.cp_index_num_contexts.restype = i32
+    lib.cp_index_num_contexts.argtypes = [vp]
+    lib.cp_index_num_nodes.restype = i32
+    lib.cp_index_num_nodes.argtypes = [vp]
+    lib.cp_index_aligned.restype = ctypes.c_int
+    lib.cp_index_aligned.argtypes = [vp, i32, i32p, i32, i32p]
+    lib.cp_index_path.restype = ctypes.c_int
+    lib.cp_index_path.argtypes = [vp, i32, i32p, i32, i32p]
+    lib.cp_index_leaf.restype = ctypes.c_int
+    lib.cp_index_leaf.argtypes = [vp, i32, i32p]
+    lib.cp_index_node.restype = ctypes.c_int
+    lib.cp_index_node.argtypes = [vp, i32, i32p, i32p, i32p, f64p, i32p, i32p, i32, i32p]
+    lib.cp_index_children.restype = ctypes.c_int
+    lib.cp_index_children.argtypes = [vp, i32, i32p, i32, i32p]
+    lib.cp_index_search.restype = ctypes.c_int
+    lib.cp_index_search.argtypes = [vp, i32p, i32, i32p, i32, i32p, i32p]
+    lib.cp_index_insert.restype = ctypes.c_int
+    lib.cp_index_insert.argtypes = [vp, i32p, i32, i32p, i32p, i32, i32p]
+    lib.cp_index_schedule.restype = ctypes.c_int
+    lib.cp_index_schedule.argtypes = [i32p, i32p, i32, i32, i32p]
     lib.cp_status_string.restype = ctypes.c_char_p
     lib.cp_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -176,3 +207,131 @@ def cp_probe_mfma_sink_floats() -> int:
 
 def cp_probe_mfma_flops(iters: int) -> float:
     return float(load_library().cp_probe_mfma_flops(int(iters)))
+
+
+# ---- context index (host memory only; numpy arrays in, numpy arrays / lists out) -------------
+def _i32_array(a):
+    import numpy as np
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _check_index(st: int, what: str) -> None:
+    if st != CP_OK:
+        raise CpError(st, what)
+
+
+def cp_index_distinct(contexts, lens):
+    """first_of [n] int32 and the number of distinct contexts."""
+    import numpy as np
+    contexts, cptr = _i32_array(contexts)
+    lens, lptr = _i32_array(lens)
+    n, stride = contexts.shape
+    first_of = np.zeros(n, dtype=np.int32)
+    m = ctypes.c_int32(0)
+    _check_index(load_library().cp_index_distinct(cptr, lptr, n, stride,
+                                                  first_of.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                                  ctypes.byref(m)), "cp_index_distinct")
+    return first_of, int(m.value)
+
+
+class ContextIndex:
+    """Owner of a cp_index handle.  Every method is one C call plus argument marshalling."""
+
+    PATH_CAP = 4096
+
+    def __init__(self, contexts, lens, alpha: float, dist=None):
+        import numpy as np
+        contexts, cptr = _i32_array(contexts)
+        lens, lptr = _i32_array(lens)
+        n, stride = contexts.shape
+        dptr, m = None, 0
+        if dist is not None:
+            dist = np.ascontiguousarray(dist, dtype=np.float32)
+            m = dist.shape[0]
+            dptr = dist.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+        self._lib = load_library()
+        self._h = ctypes.c_void_p()
+        _check_index(self._lib.cp_index_build(cptr, lptr, n, stride, float(alpha), dptr, m,
+                                              ctypes.byref(self._h)), "cp_index_build")
+
+    def close(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h.value:
+            self._lib.cp_index_free(self._h)
+            self._h = ctypes.c_void_p()
+
+    __del__ = close
+
+    def num_contexts(self) -> int:
+        return int(self._lib.cp_index_num_contexts(self._h))
+
+    def num_nodes(self) -> int:
+        return int(self._lib.cp_index_num_nodes(self._h))
+
+    def _list(self, fn, what, *args):
+        buf = (ctypes.c_int32 * self.PATH_CAP)()
+        n = ctypes.c_int32(0)
+        _check_index(fn(self._h, *args, buf, self.PATH_CAP, ctypes.byref(n)), what)
+        return [int(buf[i]) for i in range(n.value)]
+
+    def aligned(self, i: int):
+        return self._list(self._lib.cp_index_aligned, "cp_index_aligned", int(i))
+
+    def path(self, i: int):
+        return self._list(self._lib.cp_index_path, "cp_index_path", int(i))
+
+    def leaf(self, i: int) -> int:
+        node = ctypes.c_int32(0)
+        _check_index(self._lib.cp_index_leaf(self._h, int(i), ctypes.byref(node)), "cp_index_leaf")
+        return int(node.value)
+
+    def children(self, node: int):
+        return self._list(self._lib.cp_index_children, "cp_index_children", int(node))
+
+    def node(self, node: int) -> dict:
+        parent, leaf, freq, nch, n = (ctypes.c_int32(0) for _ in range(5))
+        created = ctypes.c_double(0.0)
+        buf = (ctypes.c_int32 * self.PATH_CAP)()
+        _check_index(self._lib.cp_index_node(self._h, int(node), ctypes.byref(parent), ctypes.byref(leaf),
+                                             ctypes.byref(freq), ctypes.byref(created), ctypes.byref(nch), buf,
+                                             self.PATH_CAP, ctypes.byref(n)), "cp_index_node")
+        return {"parent": int(parent.value), "leaf": bool(leaf.value), "freq": int(freq.value),
+                "created_at": float(created.value), "num_children": int(nch.value),
+                "docs": [int(buf[i]) for i in range(n.value)]}
+
+    def search(self, ids):
+        ids, iptr = _i32_array(ids)
+        buf = (ctypes.c_int32 * self.PATH_CAP)()
+        n, node = ctypes.c_int32(0), ctypes.c_int32(0)
+        _check_index(self._lib.cp_index_search(self._h, iptr, len(ids), buf, self.PATH_CAP, ctypes.byref(n),
+                                               ctypes.byref(node)), "cp_index_search")
+        return [int(buf[i]) for i in range(n.value)], int(node.value)
+
+    def insert(self, ids):
+        import numpy as np
+        ids, iptr = _i32_array(ids)
+        aligned = np.zeros(max(len(ids), 1), dtype=np.int32)
+        buf = (ctypes.c_int32 * self.PATH_CAP)()
+        n = ctypes.c_int32(0)
+        _check_index(self._lib.cp_index_insert(self._h, iptr, len(ids),
+                                               aligned.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), buf,
+                                               self.PATH_CAP, ctypes.byref(n)), "cp_index_insert")
+        return [int(x) for x in aligned[:len(ids)]], [int(buf[i]) for i in range(n.value)]
+
+
+def cp_index_schedule(paths):
+    """Execution order (list of indices) for a list of search paths."""
+    import numpy as np
+    n = len(paths)
+    stride = max([len(p) for p in paths] + [1])
+    P = np.zeros((max(n, 1), stride), dtype=np.int32)
+    L = np.zeros(max(n, 1), dtype=np.int32)
+    for i, p in enumerate(paths):
+        P[i, :len(p)] = p
+        L[i] = len(p)
+    order = np.zeros(max(n, 1), dtype=np.int32)
+    _check_index(load_library().cp_index_schedule(P.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                                  L.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), n, stride,
+                                                  order.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))),
+                 "cp_index_schedule")
+    return [int(x) for x in order[:n]]

@@ -220,3 +220,20 @@ def test_config3_scaled_full_compare(H):
     w = W.config3_rag_zipf(batch=12, block=64, topk=6, pool_ids=60, query=16, Hq=8, Hkv=2)
     assert max(w.notes["matched_blocks"]) >= 1
     _check(H.gpu_attention(w), oracle.attention_of(w), "config3 scaled")
+
+
+def test_rag_batch_aligned_and_scheduled_by_the_context_index(H):
+    """A small RAG batch whose block order and execution order come from the context index
+    library (paper, Sections 4-5), then attention over the resulting aliased prefix pages."""
+    import paper_2511_03475_amd as cp
+    picks = W.rag_zipf_picks(seed=321, batch=12, topk=6, pool_ids=40)
+    C = np.array(picks, np.int32)
+    idx = cp.ContextIndex(C, np.full(len(picks), 6, np.int32), 0.001)
+    aligned = [idx.aligned(i) for i in range(len(picks))]
+    order = cp.cp_index_schedule([idx.path(i) for i in range(len(picks))])
+    idx.close()
+    w = W.rag_batch_from_blocks("rag_index", 321, aligned, block=64, query=16, Hq=8, Hkv=2, order=order)
+    plain = W.rag_batch_from_blocks("rag_plain", 321, picks, block=64, query=16, Hq=8, Hkv=2)
+    assert w.notes["token_hit_ratio"] > plain.notes["token_hit_ratio"]
+    assert sum(w.notes["matched_blocks"]) > 0
+    _check(H.gpu_attention(w), oracle.attention_of(w), "rag batch from the context index")

@@ -77,3 +77,25 @@ def test_sample_rows_cover_edges_and_every_block():
     assert {0, 1, 2, 3, 696, 697, 698, 699, 299, 300, 301, 700, 829}.issubset(s)
     for blk in range(6):
         assert any(blk * 128 <= x < min((blk + 1) * 128, 700) for x in s)
+
+
+def test_rag_batch_from_blocks_prefix_matching_and_order():
+    ctx = [[5, 6, 7], [5, 6, 9], [1], [5, 2]]
+    w = W.rag_batch_from_blocks("t", 77, ctx, block=32, query=16, Hq=4, Hkv=2)
+    assert w.notes["matched_blocks"] == [0, 2, 0, 1]
+    assert list(w.prefix_lens) == [0, 64, 0, 32] and list(w.extend_lens) == [112, 48, 48, 48]
+    # prefix pages alias the donor's pages; everything else is distinct
+    assert list(w.block_table[1, :4]) == list(w.block_table[0, :4])
+    assert list(w.block_table[3, :2]) == list(w.block_table[0, :2])
+    used = [int(p) for r in range(4) for p in w.block_table[r] if p >= 0]
+    assert len(set(used)) == w.num_pages and max(used) == w.num_pages - 1
+    # execution order: request r of the batch is ctx[order[r]]
+    w2 = W.rag_batch_from_blocks("t", 77, ctx, block=32, query=16, Hq=4, Hkv=2, order=[3, 1, 0, 2])
+    assert w2.notes["matched_blocks"] == [0, 1, 2, 0]
+    assert list(w2.prefix_lens) == [0, 32, 64, 0]
+
+
+def test_config3_is_the_frequency_sorted_special_case():
+    picks = W.rag_zipf_picks(batch=6, topk=4, pool_ids=12)
+    assert len(picks) == 6 and all(len(set(p)) == 4 for p in picks)
+    assert W.rag_zipf_picks(batch=6, topk=4, pool_ids=12) == picks, "seeded"

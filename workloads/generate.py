@@ -198,55 +198,72 @@ def config2_rag_fixed(seed: int = BASE_SEED + 2, batch: int = 8, block: int = 10
                      cached_region_pages + batch * ep, rngs=rngs)
 
 
-def config3_rag_zipf(seed: int = BASE_SEED + 3, batch: int = 32, block: int = 1024,
-                     topk: int = 10, pool_ids: int = 2000, zipf_s: float = 1.1,
-                     query: int = 128, Hq: int = 32, Hkv: int = 8) -> Workload:
-    """RAG batch with Zipf block popularity and frequency-sorted block order.
-
-    Each request draws `topk` distinct block ids with weight rank^-s; blocks are
-    reordered by descending count over the batch (ties: smaller id first); the cached
-    prefix of request r is the longest leading block sequence shared with any earlier
-    request, and its pages alias that request's physical pages.
-    """
-    rngs = _streams(seed)
-    rs = rngs[5]
+def rag_zipf_picks(seed: int = BASE_SEED + 3, batch: int = 32, topk: int = 10,
+                   pool_ids: int = 2000, zipf_s: float = 1.1) -> List[List[int]]:
+    """The retrieved block ids of a RAG batch, in retrieval order: each request draws `topk`
+    distinct ids with weight rank^-s."""
+    rs = _streams(seed)[5]
     w = (np.arange(pool_ids, dtype=np.float64) + 1.0) ** (-zipf_s)
     w /= w.sum()
-    picks = [rs.choice(pool_ids, size=topk, replace=False, p=w) for _ in range(batch)]
-    counts = np.bincount(np.concatenate(picks), minlength=pool_ids)
-    aligned: List[List[int]] = [sorted((int(i) for i in p), key=lambda i: (-int(counts[i]), i))
-                                for p in picks]
+    return [[int(i) for i in rs.choice(pool_ids, size=topk, replace=False, p=w)] for _ in range(batch)]
+
+
+def rag_batch_from_blocks(name: str, seed: int, contexts: List[List[int]], block: int = 1024,
+                          query: int = 128, Hq: int = 32, Hkv: int = 8,
+                          order: Optional[List[int]] = None) -> Workload:
+    """A RAG batch whose requests are given as block-id sequences, as they will be run.
+
+    Request r of the batch is contexts[order[r]] (order: execution order, default as given).
+    Its cached prefix is the longest leading block sequence it shares with any earlier request
+    of the batch (an exact prefix cache that has kept them all), and its prefix pages alias
+    that request's physical pages.  Every request ends with `query` extra tokens.
+    """
+    order = list(range(len(contexts))) if order is None else [int(i) for i in order]
+    assert sorted(order) == list(range(len(contexts)))
+    rngs = _streams(seed)
+    seqs = [contexts[i] for i in order]
+    batch = len(seqs)
     assert block % PAGE_SIZE == 0
     bp = block // PAGE_SIZE
-    n_tok = topk * block + query
-    pages_per_req = (n_tok + PAGE_SIZE - 1) // PAGE_SIZE
+    pages_of = [(len(c) * block + query + PAGE_SIZE - 1) // PAGE_SIZE for c in seqs]
     matched, donor = [], []
     for r in range(batch):
         best, who = 0, -1
         for e in range(r):
             m = 0
-            while m < topk and aligned[r][m] == aligned[e][m]:
+            while m < len(seqs[r]) and m < len(seqs[e]) and seqs[r][m] == seqs[e][m]:
                 m += 1
             if m > best:
                 best, who = m, e
         matched.append(best)
         donor.append(who)
-    fresh = [pages_per_req - matched[r] * bp for r in range(batch)]
+    fresh = [pages_of[r] - matched[r] * bp for r in range(batch)]
     num_pages = int(sum(fresh))
     perm = rngs[4].permutation(num_pages)
-    table = np.full((batch, pages_per_req), -1, dtype=np.int32)
+    table = np.full((batch, max(pages_of)), -1, dtype=np.int32)
     pos = 0
     for r in range(batch):
         a = matched[r] * bp
         if a:
             table[r, :a] = table[donor[r], :a]
-        table[r, a:] = perm[pos:pos + fresh[r]]
+        table[r, a:pages_of[r]] = perm[pos:pos + fresh[r]]
         pos += fresh[r]
     P = [m * block for m in matched]
-    E = [(topk - m) * block + query for m in matched]
-    hit = float(sum(P)) / float(batch * n_tok)
-    return _assemble("rag_zipf", seed, Hq, Hkv, P, E, table, num_pages, rngs=rngs,
-                     notes={"matched_blocks": matched, "token_hit_ratio": hit})
+    E = [(len(seqs[r]) - matched[r]) * block + query for r in range(batch)]
+    hit = float(sum(P)) / float(sum(P) + sum(E))
+    return _assemble(name, seed, Hq, Hkv, P, E, table, num_pages, rngs=rngs,
+                     notes={"matched_blocks": matched, "token_hit_ratio": hit, "order": order})
+
+
+def config3_rag_zipf(seed: int = BASE_SEED + 3, batch: int = 32, block: int = 1024,
+                     topk: int = 10, pool_ids: int = 2000, zipf_s: float = 1.1,
+                     query: int = 128, Hq: int = 32, Hkv: int = 8) -> Workload:
+    """RAG batch with Zipf block popularity and frequency-sorted block order: the blocks of
+    each request are reordered by descending count over the batch (ties: smaller id first)."""
+    picks = rag_zipf_picks(seed, batch, topk, pool_ids, zipf_s)
+    counts = np.bincount(np.concatenate([np.asarray(p) for p in picks]), minlength=pool_ids)
+    aligned = [sorted(p, key=lambda i: (-int(counts[i]), i)) for p in picks]
+    return rag_batch_from_blocks("rag_zipf", seed, aligned, block, query, Hq, Hkv)
 
 
 def config4_long_context(seed: int = BASE_SEED + 4, batch: int = 4, prefix: int = 24576,
