@@ -28,8 +28,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # WRITE_SIZE x 1.0, scale factors from a 1 GiB device copy in the same run), valid only for the
 # kernel source they were taken with: reported as null as soon as that source changes.
 TRAFFIC = {
-    "source_sha256_16": "080215f6623107fd",
-    "long_context_32k": (2130217 * 2.0 + 524290) * 1024.0,
+    "source_sha256_16": "fc42c6466621f6da",
+    "long_context_32k": (2130257 * 2.0 + 524300) * 1024.0,
 }
 
 
@@ -56,6 +56,10 @@ def _workload(name: str):
         "ctx128k_reuse": lambda: W.config5_128k(True),
         "short_extend_probe": W.probe_short_extend,
         "rag_zipf_context_index": rag_zipf_context_index,
+        # decode shapes (one new token per request): the memory-bound end of the same path
+        "decode_b32_p10k": lambda: W.make_uniform("decode_b32_p10k", W.BASE_SEED + 7, 32, 32, 8, 10240, 1),
+        "decode_b32_p10k_e16": lambda: W.make_uniform("decode_b32_p10k_e16", W.BASE_SEED + 8, 32, 32, 8, 10240, 16),
+        "decode_b1_p128k": lambda: W.make_uniform("decode_b1_p128k", W.BASE_SEED + 9, 1, 32, 8, 131072, 1),
         "rag_zipf_as_retrieved": lambda: W.rag_batch_from_blocks("rag_zipf_as_retrieved", W.BASE_SEED + 3,
                                                                  W.rag_zipf_picks()),
     }
@@ -343,7 +347,8 @@ def main():
     extra = []
     if not args.no_extra:
         for name in ("tiny_extend", "rag_fixed", "rag_zipf", "rag_zipf_as_retrieved", "rag_zipf_context_index",
-                     "long_context_32k", "ctx128k_zero_reuse", "ctx128k_reuse", "short_extend_probe"):
+                     "long_context_32k", "ctx128k_zero_reuse", "ctx128k_reuse", "short_extend_probe",
+                     "decode_b32_p10k", "decode_b32_p10k_e16", "decode_b1_p128k"):
             if name == args.workload:
                 extra.append({k: head[k] for k in head})
                 continue

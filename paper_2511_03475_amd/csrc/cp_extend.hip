@@ -201,7 +201,38 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     const int64_t v_plane = (int64_t)p.Hkv * kPS * kD; // K slab -> V slab inside a page
     const int64_t row_pitch = (int64_t)p.Hkv * kD;     // elements between rows of k_new
 
+    // Full tiles (no row to clamp) take a shorter address path: a scalar base per page, or per
+    // load step of the suffix, plus a per-lane byte offset that never changes.
+    typedef const __attribute__((address_space(1))) char *gptr;
+    const uint32_t row_bytes = (uint32_t)row_pitch * 2u;
+    const uint32_t pg_lane_k = (uint32_t)(((ld_row & 15) * kD + ld_chunk * 8) * 2); // inside a page's K slab
+    const uint32_t pg_lane_v = pg_lane_k + (uint32_t)(v_plane * 2);                  // same row, V slab
+    const uint32_t sfx_lane = (uint32_t)ld_row * row_bytes + (uint32_t)ld_chunk * 16u;
+    const uint64_t page_bytes = (uint64_t)p.Hkv * (2u * kPS * kD * 2u);
+    const gptr pages_head = (gptr)p.kv_pages + (int64_t)kvh * (kPS * kD * 2);
+    const gptr knew_head = (gptr)p.k_new + ((int64_t)cu * p.Hkv + kvh) * (kD * 2);
+    const gptr vnew_head = (gptr)p.v_new + ((int64_t)cu * p.Hkv + kvh) * (kD * 2);
     auto load_tile = [&](int kt, TileRegs &tr) {
+        if (kt < np_tiles && (kt + 1) * kBN <= P) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const uint32_t page = (uint32_t)table[kt * (kBN / kPS) + 2 * i + (wave >> 2)];
+                const gptr base = pages_head + (uint64_t)page * page_bytes;
+                tr.k[i] = *(const __attribute__((address_space(1))) u32x4 *)(base + pg_lane_k);
+                tr.v[i] = *(const __attribute__((address_space(1))) u32x4 *)(base + pg_lane_v);
+            }
+            return;
+        }
+        if (kt >= np_tiles && (kt - np_tiles + 1) * kBN <= E) {
+            const int64_t tile_off = (int64_t)(kt - np_tiles) * kBN * row_bytes;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int64_t off = tile_off + (int64_t)(i * kLoadRows) * row_bytes;
+                tr.k[i] = *(const __attribute__((address_space(1))) u32x4 *)(knew_head + off + sfx_lane);
+                tr.v[i] = *(const __attribute__((address_space(1))) u32x4 *)(vnew_head + off + sfx_lane);
+            }
+            return;
+        }
         const uint16_t *ks[2];
         const uint16_t *vs[2];
         if (kt < np_tiles) {
@@ -381,8 +412,10 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
         if (need_mask) mask_tile(suffix ? (row_i - key0 + 1) : (P - key0), s);
     };
     // a suffix tile entirely above this wavefront's rows shows it nothing, and neither does
-    // any later tile
-    auto skipped = [&](int kt) { return kt >= np_tiles && tile_key0(kt) > wave_row0 + 31; };
+    // any later tile; a wavefront whose 32 rows all lie past the end of the request (short
+    // extends, decode) computes nothing at all and only takes part in the cooperative loads
+    const bool no_rows = wave_row0 >= E;
+    auto skipped = [&](int kt) { return no_rows || (kt >= np_tiles && tile_key0(kt) > wave_row0 + 31); };
 
     PTile pb_a, pb_b; // probabilities of the previous / the current tile
 

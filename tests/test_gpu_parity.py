@@ -237,3 +237,18 @@ def test_rag_batch_aligned_and_scheduled_by_the_context_index(H):
     assert w.notes["token_hit_ratio"] > plain.notes["token_hit_ratio"]
     assert sum(w.notes["matched_blocks"]) > 0
     _check(H.gpu_attention(w), oracle.attention_of(w), "rag batch from the context index")
+
+
+@pytest.mark.parametrize("B,P,E,G,Hkv", [
+    (4, 2048, 1, 4, 2),       # decode: one new token, several heads packed into a workgroup
+    (3, [4097, 15, 700], [1, 1, 1], 8, 1),
+    (2, 3000, 16, 4, 2),      # a small chunk per request
+    (1, 20000, 1, 4, 1),      # one long request: many splits
+])
+def test_decode_shapes(H, B, P, E, G, Hkv):
+    """One or a few new tokens per request over a long cached prefix: wavefronts without valid
+    rows only help loading, split-K fills the device."""
+    w = W.make_uniform("decode", 131, B, G * Hkv, Hkv, P, E)
+    want = oracle.attention_of(w)
+    _check(H.gpu_attention(w), want, f"decode B={B} P={P} E={E}")
+    _check(H.gpu_attention(w, num_splits=1), want, f"decode unsplit B={B} P={P} E={E}")
