@@ -60,8 +60,10 @@ typedef struct cp_shape {
     int32_t max_pages_per_req; /* row stride of block_table; >= ceil((P_r+E_r)/PS) for all r */
     int32_t total_extend;      /* T; must equal the sum of h_extend_lens */
     float softmax_scale;       /* multiplies q.k before the softmax; finite and > 0 */
-    int32_t num_splits;        /* split-K factor over the keys: 0 = chosen by the library,
-                                  1 = never split, 2..64 = forced */
+    int32_t num_splits;        /* split-K factor over the keys: 0 = chosen by the library
+                                  (which also picks the decode-shaped kernel when every request
+                                  has G * E_r <= 64 rows per KV head), 1 = never split,
+                                  2..64 = forced */
     const int32_t *h_prefix_lens; /* HOST, length B, each >= 0 */
     const int32_t *h_extend_lens; /* HOST, length B, each >= 0 */
 } cp_shape;
@@ -73,7 +75,8 @@ typedef struct cp_shape {
  */
 size_t cp_workspace_bytes(const cp_shape *shape);
 
-/* The split-K factor cp_extend_attention will use for this shape (>= 1; 0 if invalid). */
+/* The number of key ranges whose partial results cp_extend_attention will merge for this shape
+ * (1 = no split; up to 64 when forced, up to 256 when chosen by the library; 0 if invalid). */
 int32_t cp_num_splits(const cp_shape *shape);
 
 /*

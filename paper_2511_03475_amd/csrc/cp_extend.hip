@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "cp_extend.h"
@@ -57,6 +58,7 @@ struct AttnParams {
     float *part_ml; // [nsplit][T][Hq][2]   running max (log2 domain) and sum
     int32_t batch, Hq, Hkv, G, max_pages, T;
     int32_t nsplit;
+    int32_t dec_row_blocks; // decode kernel: blocks of 32 (head, token) rows per (request, KV head)
     int32_t items_per_head; // work units per KV head * nsplit
     int32_t total_items;    // items_per_head * Hkv
     int32_t items_per_xcd;  // ceil(total_items / 8)
@@ -504,23 +506,39 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
 }
 
 // out[row, head, :] = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max_s m_s).
-// 32 threads per (row, head), 4 consecutive d each.
-__global__ __launch_bounds__(256) void merge_splits_kernel(const float *__restrict__ part_o,
-                                                           const float *__restrict__ part_ml,
-                                                           uint16_t *__restrict__ out,
-                                                           int64_t n_rh, int nsplit)
+// One workgroup per (row, head): eight groups of 32 threads take the splits s = g, g + 8, ...
+// (4 consecutive d per thread), then the eight partial sums are added in a fixed order, so the
+// result is reproducible.  Entries with l_s = 0 (empty splits) are skipped.
+constexpr int kMergeGroups = 8;
+__global__ __launch_bounds__(32 * kMergeGroups) void merge_splits_kernel(const float *__restrict__ part_o,
+                                                                          const float *__restrict__ part_ml,
+                                                                          uint16_t *__restrict__ out,
+                                                                          int64_t n_rh, int nsplit)
 {
-    const int64_t rh = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);
-    if (rh >= n_rh) return;
-    const int d4 = (threadIdx.x & 31) * 4;
-    float m_star = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) {
+    __shared__ float s_max[kMergeGroups];
+    __shared__ float s_den[kMergeGroups];
+    __shared__ f32x4 s_acc[kMergeGroups][32];
+    const int64_t rh = blockIdx.x;
+    const int g = threadIdx.x >> 5, t = threadIdx.x & 31;
+    const int d4 = t * 4;
+    // maximum over all splits: every thread scans a strided share, then a reduction inside the
+    // group of 32 (lanes of one wavefront) and across groups through LDS
+    float m = -INFINITY;
+    for (int s = threadIdx.x; s < nsplit; s += 32 * kMergeGroups) {
         const float *ml = part_ml + ((int64_t)s * n_rh + rh) * 2;
-        if (ml[1] > 0.f) m_star = fmaxf(m_star, ml[0]);
+        if (ml[1] > 0.f) m = fmaxf(m, ml[0]);
     }
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 32));
+    if (t == 0) s_max[g] = m;
+    __syncthreads();
+    float m_star = s_max[0];
+#pragma unroll
+    for (int i = 1; i < kMergeGroups; ++i) m_star = fmaxf(m_star, s_max[i]);
+
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float denom = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
+    for (int s = g; s < nsplit; s += kMergeGroups) {
         const float *ml = part_ml + ((int64_t)s * n_rh + rh) * 2;
         const float ls = ml[1];
         if (ls > 0.f) {
@@ -530,11 +548,247 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(const float *__restri
             denom += ls * w;
         }
     }
+    s_acc[g][t] = acc;
+    if (t == 0) s_den[g] = denom;
+    __syncthreads();
+    if (g != 0) return;
+#pragma unroll
+    for (int i = 1; i < kMergeGroups; ++i) {
+        acc += s_acc[i][t];
+        denom += s_den[i];
+    }
     const float inv = denom > 0.f ? 1.f / denom : 0.f;
     bf16x4 y;
 #pragma unroll
     for (int e = 0; e < 4; ++e) y[e] = (__bf16)(acc[e] * inv);
     *reinterpret_cast<bf16x4 *>(out + rh * kD + d4) = y;
+}
+
+// ---- decode-shaped calls ------------------------------------------------------------------
+// When every request brings so few new tokens that all its rows for one KV head (G heads x E_r
+// tokens) fit a few 32-column MFMA tiles, the call is bound by reading the cached K/V once,
+// and the row-tiled kernel above wastes its wavefronts (most hold no valid row) and keeps too
+// little in flight.  This kernel turns the work around: a wavefront is the unit, owns 32 rows
+// of one (request, KV head) and a contiguous chunk of the keys, and runs alone - no barrier, no
+// shared tile.  Per block of 32 keys it loads the K and V rows with fully coalesced 16-byte
+// loads (one instruction = four whole rows), stages them in registers while the previous block
+// is computed, and passes them through a private LDS area from which the MFMA operands are read
+// (K rows as they are, V rows transposed).  Every wavefront writes an unnormalised partial
+// (m, l, O) and merge_splits_kernel combines them, exactly as for split-K.  Prefix and suffix
+// keys form one sequence of N = P + E keys; blocks inside the prefix take their two pages from
+// the block table with scalar loads, the last blocks resolve every row on its own.
+constexpr int kDecRows = 32;            // (head, token) rows per wavefront
+constexpr int kDecMaxRowBlocks = 2;     // row blocks per (request, KV head): G x E_r <= 64 (beyond, the row-tiled kernel is faster)
+constexpr int kDecWaves = 4;            // wavefronts per workgroup (independent of each other)
+constexpr int kDecPitchK = 272;         // LDS bytes per K row / V row (256 + padding, as above)
+constexpr int kDecPitchV = 320;
+constexpr int kDecLdsK = 32 * kDecPitchK;
+constexpr int kDecLdsPerWave = kDecLdsK + 32 * kDecPitchV;
+constexpr int kDecMaxChunks = 256;      // key chunks (= partial results) per (request, KV head)
+
+struct DecBlock { // one block of 32 keys as loaded: piece i is row (lane / 16) + 4 i, chunk lane % 16
+    u32x4 k[8];
+    u32x4 v[8];
+};
+
+__global__ __launch_bounds__(kDecWaves * 64, 2) void decode_attn_kernel(const AttnParams p)
+{
+    __shared__ __attribute__((aligned(16))) char lds[kDecWaves * kDecLdsPerWave];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int j = lane & 31; // (head, token) row of the accumulators; key row of the K operand
+    const int h = lane >> 5;
+    char *const lds_k = lds + wave * kDecLdsPerWave;
+    char *const lds_v = lds_k + kDecLdsK;
+
+    // work unit: row block fastest (neighbouring wavefronts then read the same keys), then key
+    // chunk, KV head, request
+    const int64_t unit = (int64_t)blockIdx.x * kDecWaves + wave;
+    const int rb = (int)(unit % p.dec_row_blocks);
+    const int64_t uc = unit / p.dec_row_blocks;
+    const int chunk = (int)(uc % p.nsplit);
+    const int64_t rk = uc / p.nsplit;
+    const int kvh = (int)(rk % p.Hkv);
+    const int r = (int)(rk / p.Hkv);
+    if (r >= p.batch) return;
+    const int E = p.extend_lens[r];
+    if (E <= 0) return;
+    const int P = p.prefix_lens[r];
+    int cu = 0;
+    for (int i = 0; i < r; ++i) cu += p.extend_lens[i];
+    const int N = P + E;
+    const int nblk = (N + 31) >> 5;
+    const int per = (nblk + p.nsplit - 1) / p.nsplit;
+    const int b0 = chunk * per;
+    const int b1 = min(nblk, b0 + per);
+
+    // row 32 rb + j of the (request, KV head) is token e of head hg of the group; rows beyond
+    // G E are padding
+    if (rb * kDecRows >= p.G * E) return;
+    const int row = rb * kDecRows + j;
+    const bool row_valid = row < p.G * E;
+    const int hg = row_valid ? row / E : 0;
+    const int e = row_valid ? row - hg * E : 0;
+    const int head = kvh * p.G + hg;
+    const int64_t out_row = cu + e;
+    const int64_t prow = ((int64_t)chunk * p.T + out_row) * p.Hq + head;
+    if (b0 >= b1) { // nothing to do for this chunk: the merge skips entries whose sum is zero
+        if (row_valid && h == 0) {
+            p.part_ml[prow * 2] = -INFINITY;
+            p.part_ml[prow * 2 + 1] = 0.f;
+        }
+        return;
+    }
+
+    // Q fragments, B operand of S^T = K Q^T: lane (row j, h) holds q[row][16 kk + 8 h .. + 8)
+    u32x4 qf[8];
+    {
+        const uint16_t *qp = p.q + (out_row * p.Hq + head) * kD + 8 * h;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) qf[kk] = *(const __attribute__((address_space(1))) u32x4 *)(qp + 16 * kk);
+    }
+
+    // loads: lane covers rows ld_sub + 4 i (i = 0..7) of the block, 16-byte chunk ld_chunk
+    const int ld_sub = lane >> 4, ld_chunk = lane & 15;
+    const __attribute__((address_space(4))) int32_t *table =
+        (const __attribute__((address_space(4))) int32_t *)(p.block_table + (int64_t)r * p.max_pages);
+    const int64_t v_plane = (int64_t)p.Hkv * kPS * kD;
+    const int64_t page_stride = 2 * v_plane;
+    const uint16_t *pages_head = p.kv_pages + (int64_t)kvh * (kPS * kD) + ld_chunk * 8;
+    auto load_block = [&](int b, DecBlock &blk) {
+        if (b * 32 + 32 <= P) {
+            // inside the prefix: rows 0..15 in page 2 b, rows 16..31 in page 2 b + 1
+            const int64_t pg[2] = {table[2 * b], table[2 * b + 1]};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint16_t *krow = pages_head + pg[i >> 2] * page_stride + ((ld_sub + 4 * i) & 15) * kD;
+                blk.k[i] = *(const __attribute__((address_space(1))) u32x4 *)(krow);
+                blk.v[i] = *(const __attribute__((address_space(1))) u32x4 *)(krow + v_plane);
+            }
+        } else {
+            // last blocks: every row resolves its own key (clamped to the last one; masked below)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int key = min(b * 32 + ld_sub + 4 * i, N - 1);
+                const uint16_t *krow, *vrow;
+                if (key < P) {
+                    krow = pages_head + (int64_t)p.block_table[(int64_t)r * p.max_pages + (key >> 4)] * page_stride +
+                           (key & 15) * kD;
+                    vrow = krow + v_plane;
+                } else {
+                    const int64_t off = ((int64_t)(cu + key - P) * p.Hkv + kvh) * kD + ld_chunk * 8;
+                    krow = p.k_new + off;
+                    vrow = p.v_new + off;
+                }
+                blk.k[i] = *(const __attribute__((address_space(1))) u32x4 *)(krow);
+                blk.v[i] = *(const __attribute__((address_space(1))) u32x4 *)(vrow);
+            }
+        }
+    };
+    const int st_k = ld_sub * kDecPitchK + ld_chunk * 16;
+    const int st_v = ld_sub * kDecPitchV + ld_chunk * 16;
+    auto store_block = [&](const DecBlock &blk) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            *reinterpret_cast<u32x4 *>(lds_k + st_k + 4 * i * kDecPitchK) = blk.k[i];
+            *reinterpret_cast<u32x4 *>(lds_v + st_v + 4 * i * kDecPitchV) = blk.v[i];
+        }
+    };
+    // operand reads, as in the kernel above
+    const int k_lane = j * kDecPitchK + h * 16;
+    const int v_lane = (4 * h + ((lane & 15) >> 2)) * kDecPitchV + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
+
+    f32x16 o[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f; // log2 domain; sum over this half-wave's keys
+    const float c = p.scale_log2;
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+
+    DecBlock blk;
+    load_block(b0, blk);
+    for (int b = b0; b < b1; ++b) {
+        // block b: registers -> private LDS (one wavefront's LDS operations are served in order,
+        // so these writes come after the reads of block b - 1), then block b + 1 into flight
+        store_block(blk);
+        if (b + 1 < b1) load_block(b + 1, blk);
+        f32x16 s;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            const u32x4 a = *reinterpret_cast<const u32x4 *>(lds_k + k_lane + kk * 32);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                         __builtin_bit_cast(bf16x8, qf[kk]), s, 0, 0, 0);
+        }
+        // accumulator element v is key 32 b + 8 (v / 4) + 4 h + v % 4; row j sees keys <= P + e
+        if (b * 32 + 31 > P) {
+            const int vis = P + e - b * 32 - 4 * h; // visible: 8 (v / 4) + v % 4 <= vis
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (8 * (v >> 2) + (v & 3) > vis) s[v] = -INFINITY;
+        }
+        float mx = s[0];
+#pragma unroll
+        for (int v = 1; v + 1 < 16; v += 2) mx = fmaxf(fmaxf(mx, s[v]), s[v + 1]);
+        mx = halfwave_max(fmaxf(mx, s[15]));
+        const float m_new = fmaxf(m_run, mx * c);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = fast_exp2(m_run - m_use);
+        u32x4 pb[2];
+        float psum = 0.f;
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                f32x2 x;
+                x[0] = fast_exp2(fmaf(s[8 * u + 2 * w], c, -m_use));
+                x[1] = fast_exp2(fmaf(s[8 * u + 2 * w + 1], c, -m_use));
+                const bf16x2 y = __builtin_convertvector(x, bf16x2);
+                psum = __builtin_amdgcn_fdot2_f32_bf16(y, ones, psum, false);
+                pb[u][w] = __builtin_bit_cast(unsigned, y);
+            }
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+        }
+        // O^T += V^T P^T: 2 steps of 16 keys x 4 blocks of 32 d
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                const char *a = lds_v + v_lane + db * 64 + ks * 16 * kDecPitchV;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4 *)(a));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4 *)(a + 8 * kDecPitchV));
+                const s16x8 vv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv),
+                                                                 __builtin_bit_cast(bf16x8, pb[ks]), o[db], 0, 0, 0);
+            }
+    }
+
+    // partial result of this chunk; o[db][v] is O^T[d = db*32 + 8*(v/4) + 4*h + v%4][row j]
+    const float l_tot = halfwave_sum(l_run);
+    if (!row_valid) return;
+    float *po = p.part_o + prow * kD;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            f32x4 x = {o[db][4 * gq], o[db][4 * gq + 1], o[db][4 * gq + 2], o[db][4 * gq + 3]};
+            *reinterpret_cast<f32x4 *>(po + db * 32 + 8 * gq + 4 * h) = x;
+        }
+    if (h == 0) {
+        p.part_ml[prow * 2] = m_run;
+        p.part_ml[prow * 2 + 1] = l_tot;
+    }
 }
 
 // One workgroup copies 16 consecutive packed rows; one thread moves 16 bytes at a time.
@@ -584,6 +838,8 @@ struct Plan {
     int64_t q_tiles;   // work units per KV head: row tiles x head groups, summed over requests
     int32_t max_key_tiles;
     int32_t nsplit;
+    bool decode;       // few rows per (request, KV head): decode_attn_kernel
+    int32_t row_blocks; // ... in this many blocks of 32 rows
 };
 
 int num_cus()
@@ -637,7 +893,30 @@ int validate(const cp_shape *s)
 
 Plan make_plan(const cp_shape *s)
 {
-    Plan pl{0, 0, 1};
+    Plan pl{0, 0, 1, false, 1};
+    const int G = s->num_q_heads / s->num_kv_heads;
+    int64_t max_e = 0, max_n = 0;
+    for (int r = 0; r < s->batch; ++r) {
+        if (s->h_extend_lens[r] == 0) continue;
+        max_e = std::max<int64_t>(max_e, s->h_extend_lens[r]);
+        max_n = std::max<int64_t>(max_n, (int64_t)s->h_prefix_lens[r] + s->h_extend_lens[r]);
+    }
+    if (s->num_splits == 0 && max_e > 0 && max_e * G <= kDecRows * kDecMaxRowBlocks) {
+        // Decode-shaped: one wavefront per (request, KV head, 32 rows, key chunk).  Enough chunks
+        // for 8 wavefronts per CU, at least 2 blocks of 32 keys each, a multiple of the workgroup
+        // size.
+        pl.row_blocks = (int32_t)((max_e * G + kDecRows - 1) / kDecRows);
+        const int64_t pairs = (int64_t)s->batch * s->num_kv_heads * pl.row_blocks;
+        int64_t ns = (8LL * num_cus() + pairs - 1) / pairs;
+        const int64_t cap = ((max_n + 31) / 32 + 1) / 2;
+        if (ns > cap) ns = cap;
+        ns = (ns + kDecWaves - 1) / kDecWaves * kDecWaves;
+        if (ns > kDecMaxChunks) ns = kDecMaxChunks;
+        if (ns < kDecWaves) ns = kDecWaves;
+        pl.nsplit = (int32_t)ns;
+        pl.decode = true;
+        return pl;
+    }
     for (int r = 0; r < s->batch; ++r) {
         const int64_t P = s->h_prefix_lens[r], E = s->h_extend_lens[r];
         if (E == 0) continue;
@@ -720,6 +999,8 @@ int cp_extend_attention(const void *q, const void *k_new, const void *v_new, con
     const int64_t per_head = pl.q_tiles * pl.nsplit;
     const int64_t total = per_head * shape->num_kv_heads;
     if (total > INT32_MAX / 2) return CP_ERR_SHAPE;
+    const int64_t dec_units = (int64_t)shape->batch * shape->num_kv_heads * pl.nsplit * pl.row_blocks;
+    if (pl.decode && dec_units > INT32_MAX / 2) return CP_ERR_SHAPE;
 
     AttnParams p;
     p.q = static_cast<const uint16_t *>(q);
@@ -739,13 +1020,26 @@ int cp_extend_attention(const void *q, const void *k_new, const void *v_new, con
     p.max_pages = shape->max_pages_per_req;
     p.T = shape->total_extend;
     p.nsplit = pl.nsplit;
+    p.dec_row_blocks = pl.row_blocks;
     p.items_per_head = (int32_t)per_head;
     p.total_items = (int32_t)total;
     p.items_per_xcd = (int32_t)((total + kXcds - 1) / kXcds);
     p.scale_log2 = shape->softmax_scale * 1.4426950408889634f;
 
-    if (!allow_large_lds()) return CP_ERR_LAUNCH;
     hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (pl.decode) {
+        const size_t rows = (size_t)pl.nsplit * (size_t)p.T * (size_t)p.Hq;
+        const size_t o_bytes = ((rows * kD * sizeof(float) + 255) / 256) * 256;
+        p.part_o = static_cast<float *>(workspace);
+        p.part_ml = reinterpret_cast<float *>(static_cast<char *>(workspace) + o_bytes);
+        hipLaunchKernelGGL(decode_attn_kernel, dim3((unsigned)(dec_units / kDecWaves)), dim3(kDecWaves * 64), 0, hs, p);
+        if (hipGetLastError() != hipSuccess) return CP_ERR_LAUNCH;
+        const int64_t n_rh = (int64_t)p.T * p.Hq;
+        hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)n_rh), dim3(32 * kMergeGroups), 0, hs,
+                           p.part_o, p.part_ml, p.out, n_rh, pl.nsplit);
+        return hipGetLastError() == hipSuccess ? CP_OK : CP_ERR_LAUNCH;
+    }
+    if (!allow_large_lds()) return CP_ERR_LAUNCH;
     const dim3 grid((unsigned)(p.items_per_xcd * kXcds)), block(kThreads);
     if (pl.nsplit > 1) {
         const size_t rows = (size_t)pl.nsplit * (size_t)p.T * (size_t)p.Hq;
@@ -755,7 +1049,7 @@ int cp_extend_attention(const void *q, const void *k_new, const void *v_new, con
         hipLaunchKernelGGL(extend_attn_kernel<true>, grid, block, kLdsBytes, hs, p);
         if (hipGetLastError() != hipSuccess) return CP_ERR_LAUNCH;
         const int64_t n_rh = (int64_t)p.T * p.Hq;
-        hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)((n_rh + 7) / 8)), dim3(256), 0, hs,
+        hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)n_rh), dim3(32 * kMergeGroups), 0, hs,
                            p.part_o, p.part_ml, p.out, n_rh, pl.nsplit);
     } else {
         hipLaunchKernelGGL(extend_attn_kernel<false>, grid, block, kLdsBytes, hs, p);

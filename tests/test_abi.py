@@ -61,6 +61,24 @@ def test_split_plan_is_a_pure_function_of_the_shape(lib):
     assert cp.cp_num_splits(_shape([10240], [128])) == ns
 
 
+def test_decode_shaped_calls_get_a_wavefront_level_plan(lib):
+    """Few rows per (request, KV head): the library merges many wavefront-sized key chunks, a
+    multiple of the four wavefronts of a workgroup; a forced split count keeps the row-tiled
+    kernel."""
+    dec = _shape([10240] * 32, [1] * 32)
+    ns = cp.cp_num_splits(dec)
+    assert ns >= 4 and ns % 4 == 0 and ns <= 256
+    rows = ns * 32 * 32
+    assert cp.cp_workspace_bytes(dec) == rows * 128 * 4 + rows * 2 * 4
+    assert cp.cp_num_splits(_shape([10240] * 32, [1] * 32, splits=1)) == 1
+    one = cp.cp_num_splits(_shape([131072], [1]))
+    assert one % 4 == 0 and one > ns
+    tiny = cp.cp_num_splits(_shape([0, 3], [2, 1]))          # at most 2 blocks of keys per chunk
+    assert tiny == 4
+    # G * E = 4 * 17 = 68 rows per KV head is past the decode-shaped limit
+    assert cp.cp_num_splits(_shape([10240] * 64, [17] * 64)) == 1
+
+
 def test_invalid_shapes_are_rejected_on_the_host(lib):
     bad = [
         _shape([32], [32], Hq=4, Hkv=3),           # Hq % Hkv != 0

@@ -252,3 +252,46 @@ def test_decode_shapes(H, B, P, E, G, Hkv):
     want = oracle.attention_of(w)
     _check(H.gpu_attention(w), want, f"decode B={B} P={P} E={E}")
     _check(H.gpu_attention(w, num_splits=1), want, f"decode unsplit B={B} P={P} E={E}")
+
+
+@pytest.mark.parametrize("G,Hkv,P,E", [
+    (4, 2, [0, 0, 0], [1, 5, 16]),                 # no prefix at all: a single partly filled block
+    (4, 2, [31, 32, 33, 1000], [1, 2, 3, 16]),     # blocks that straddle the prefix / suffix boundary
+    (4, 2, [500, 7, 0, 4096], [9, 0, 11, 13]),     # a second row block that is partly filled; E = 0
+    (8, 1, [777, 2048], [8, 3]),                   # G x E = 64 rows
+    (1, 3, [100, 3000], [16, 1]),                  # one q head per KV head
+    (2, 2, [65, 129], [7, 16]),
+])
+def test_decode_kernel_shapes(H, G, Hkv, P, E):
+    """Calls with at most 64 rows per (request, KV head) run the wavefront-per-chunk kernel
+    (cp_num_splits is then a multiple of 4); same bar against the oracle, and close to the
+    row-tiled kernel on the same inputs."""
+    import paper_2511_03475_amd as cp
+    w = W.make_uniform("deck", 141, len(P), G * Hkv, Hkv, P, E)
+    case = H.DeviceCase(w)
+    assert cp.cp_num_splits(case.shape) % 4 == 0 and case.ws_bytes > 0
+    want = oracle.attention_of(w)
+    case.attention()
+    got = case.out_bits()
+    _check(got, want, f"decode kernel G={G} P={P} E={E}")
+    case.attention()
+    assert np.array_equal(case.out_bits(), got), "bitwise reproducible"
+    tiled = bf16_bits_to_f32(H.gpu_attention(w, num_splits=1)).astype(np.float64)
+    assert np.abs(bf16_bits_to_f32(got).astype(np.float64) - tiled).max() <= 2e-2
+
+
+def test_decode_kernel_finds_a_needle_in_a_long_prefix(H):
+    """One key far back in a 40k-token prefix dominates: every chunk but one contributes
+    almost nothing and the merge must still return that key's value."""
+    w = W.make_uniform("needle", 151, 2, 8, 2, [40000, 12345], [1, 2])
+    q = bf16_bits_to_f32(w.q)
+    pos = 23456
+    page, slot = int(w.block_table[0, pos // 16]), pos % 16
+    for kvh in range(2):
+        # key = 4 * q of head 4 kvh (the first head of the group): score ~ 4 |q|^2 * scale >> others
+        w.kv_pages[page, 0, kvh, slot, :] = f32_to_bf16_bits(4.0 * q[0, 4 * kvh, :])
+    want = oracle.attention_of(w)
+    got = H.gpu_attention(w)
+    _check(got, want, "decode needle")
+    v = bf16_bits_to_f32(w.kv_pages[page, 1, 0, slot, :]).astype(np.float64)
+    assert np.abs(bf16_bits_to_f32(got)[0, 0].astype(np.float64) - v).max() < 5e-2
