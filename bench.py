@@ -28,8 +28,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # WRITE_SIZE x 1.0, scale factors from a 1 GiB device copy in the same run), valid only for the
 # kernel source they were taken with: reported as null as soon as that source changes.
 TRAFFIC = {
-    "source_sha256_16": "fc42c6466621f6da",
-    "long_context_32k": (2130257 * 2.0 + 524300) * 1024.0,
+    "source_sha256_16": "f18b1dbbbce66a93",
+    "long_context_32k": (2130242 * 2.0 + 524290) * 1024.0,      # extend_attn_kernel
+    "decode_b32_p10k": (656156 * 2.0 + 4160) * 1024.0,          # decode_attn_kernel
 }
 
 
@@ -43,6 +44,19 @@ def measured_traffic(workload: str):
     if digest != TRAFFIC["source_sha256_16"]:
         return None
     return TRAFFIC.get(workload)
+
+
+def roofline_of(workload: str, head: dict) -> dict:
+    """Roofline entry of the dominant kernel: the matrix pipe when the call has more flops per
+    algorithmic byte than the machine balance (2.5 PFLOP/s / 8 TB/s), HBM otherwise."""
+    if head["flops"] / head["alg_bytes"] >= PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+        return {"bound": "mfma", "kernel": "extend_attn_kernel", "achieved": head["tflops_attn"],
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": head["frac_mfma_peak"],
+                "traffic": measured_traffic(workload), "avg_kernel_ms": head["attn_ms_avg"]}
+    return {"bound": "hbm", "kernel": "decode_attn_kernel + merge_splits_kernel" if head["splits"] % 4 == 0
+            else "extend_attn_kernel (+ merge_splits_kernel)", "achieved": head["gbs_attn"],
+            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": head["frac_hbm_peak"],
+            "traffic": measured_traffic(workload), "avg_kernel_ms": head["attn_ms_avg"]}
 
 
 def _workload(name: str):
@@ -168,6 +182,8 @@ def measure(name: str, steps: int, warmup: int):
         "frac_mfma_peak": flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "alg_bytes": algorithmic_bytes(w),
         "gbs_step": algorithmic_bytes(w) / (ms_step * 1e-3) / 1e9,
+        "gbs_attn": algorithmic_bytes(w) / (attn_ms * 1e-3) / 1e9,
+        "frac_hbm_peak": algorithmic_bytes(w) / (attn_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "gen_s": gen_s,
     }
     if w.notes:
@@ -374,10 +390,7 @@ def main():
                    "kv_heads": head["kv_heads"], "head_dim": 128, "page_size": 16,
                    "prefix_tokens": head["prefix_tokens"], "extend_tokens": head["extend_tokens"],
                    "step": "cp_write_kv + cp_extend_attention", "splits": head["splits"]},
-        "roofline": {"bound": "mfma", "kernel": "extend_attn_kernel",
-                     "achieved": head["tflops_attn"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": head["frac_mfma_peak"], "traffic": measured_traffic(args.workload),
-                     "avg_kernel_ms": head["attn_ms_avg"]},
+        "roofline": roofline_of(args.workload, head),
         "cpu_baseline": cpu,
     }
     if extra:
@@ -392,8 +405,11 @@ def main():
         line["context_distance"] = measure_context_distance(cpu=not args.no_cpu)
         line["context_index"] = measure_context_index(cpu=not args.no_cpu)
         ceil = measure_mfma_ceiling()
-        line["roofline"]["measured_mfma_ceiling_tflops"] = ceil
-        line["roofline"]["frac_of_measured_ceiling"] = head["tflops_attn"] / ceil["random_operands"]
+        if line["roofline"]["bound"] == "mfma":
+            line["roofline"]["measured_mfma_ceiling_tflops"] = ceil
+            line["roofline"]["frac_of_measured_ceiling"] = head["tflops_attn"] / ceil["random_operands"]
+        else:
+            line["measured_mfma_ceiling_tflops"] = ceil
     print(json.dumps(line))
 
 
