@@ -85,8 +85,26 @@ __device__ __forceinline__ float halfwave_sum(float x)
 __host__ __device__ inline int heads_per_tile(int E, int G)
 {
     int pack = 1;
-    while (pack < 8 && G % (pack * 2) == 0 && E * (pack * 2) <= kBM) pack *= 2;
+    while (pack < 8 && (G & (2 * pack - 1)) == 0 && E * (pack * 2) <= kBM) pack *= 2;
     return pack;
+}
+// Work units (row tiles x head groups) of one request for one KV head; pack = heads_per_tile.
+__host__ __device__ inline int units_of_request(int E, int G, int pack)
+{
+    if (E <= 0) return 0;
+    int shift = 0;
+    while ((1 << shift) < pack) ++shift;
+    return ((E * pack + kBM - 1) / kBM) * (G >> shift);
+}
+// Inclusive prefix sum over the 64 lanes of a wavefront.
+__device__ __forceinline__ int wave_inclusive_scan(int x, int lane)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int y = __shfl_up(x, off, 64);
+        if (lane >= off) x += y;
+    }
+    return x;
 }
 
 // K/V tile of 64 keys: each of the 512 threads stages two 16-byte chunks of K and two of V in
@@ -137,19 +155,36 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
 
     // Units of a KV head: requests in order; within a request the last (longest) row tile
     // first, and for each row tile the groups of q heads that are packed into one workgroup.
-    int r = 0, cu = 0, E = 0, t = 0, pack = 1, hgroup = 0;
-    for (; r < p.batch; ++r) {
-        E = p.extend_lens[r];
-        pack = heads_per_tile(E, p.G);
-        const int groups = p.G / pack;
-        const int nt = (E * pack + kBM - 1) / kBM; // row tiles of kBM / pack rows
-        if (unit < nt * groups) {
-            hgroup = unit % groups;
-            t = nt - 1 - unit / groups;
+    // The request that owns the unit is found 64 requests at a time: every lane takes one
+    // request, a prefix sum over the wavefront gives the first unit of each (a sequential scan
+    // costs a dependent scalar load and several integer divisions per request, ~1.5 us each).
+    int r = p.batch, cu = 0, E = 0, t = 0, pack = 1, hgroup = 0;
+    for (int base = 0; base < p.batch; base += 64) {
+        const int rr = base + lane;
+        const int e_l = rr < p.batch ? p.extend_lens[rr] : 0;
+        const int units_l = units_of_request(e_l, p.G, heads_per_tile(e_l, p.G));
+        const int incl_u = wave_inclusive_scan(units_l, lane);
+        const int incl_e = wave_inclusive_scan(e_l, lane);
+        const int total_u = __builtin_amdgcn_readlane(incl_u, 63);
+        if (unit < total_u) {
+            const int first = __builtin_ctzll(__builtin_amdgcn_ballot_w64(incl_u > unit));
+            r = base + first;
+            unit -= __builtin_amdgcn_readlane(incl_u - units_l, first);
+            cu += __builtin_amdgcn_readlane(incl_e - e_l, first);
+            E = __builtin_amdgcn_readlane(e_l, first);
             break;
         }
-        unit -= nt * groups;
-        cu += E;
+        unit -= total_u;
+        cu += __builtin_amdgcn_readlane(incl_e, 63);
+    }
+    if (r < p.batch) {
+        pack = heads_per_tile(E, p.G);
+        int shift = 0;
+        while ((1 << shift) < pack) ++shift;
+        const int groups = p.G >> shift;
+        const int nt = (E * pack + kBM - 1) / kBM; // row tiles of kBM / pack rows
+        hgroup = unit % groups;
+        t = nt - 1 - unit / groups;
     }
     if (r >= p.batch) return;
     const int P = p.prefix_lens[r];
@@ -921,7 +956,7 @@ Plan make_plan(const cp_shape *s)
         const int64_t P = s->h_prefix_lens[r], E = s->h_extend_lens[r];
         if (E == 0) continue;
         const int pack = heads_per_tile((int)E, s->num_q_heads / s->num_kv_heads);
-        pl.q_tiles += ((E * pack + kBM - 1) / kBM) * (s->num_q_heads / s->num_kv_heads / pack);
+        pl.q_tiles += units_of_request((int)E, s->num_q_heads / s->num_kv_heads, pack);
         const int64_t kt = (P + kBN - 1) / kBN + (E + kBN - 1) / kBN;
         if (kt > pl.max_key_tiles) pl.max_key_tiles = (int32_t)kt;
     }
