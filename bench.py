@@ -304,6 +304,38 @@ def measure_context_index(n: int = 2000, k: int = 15, cpu: bool = True):
     return res
 
 
+def measure_context_dedup(cpu: bool = True):
+    """Multi-turn de-duplication (paper, Section 6) on a synthetic retrieval trace: host library,
+    bytes of context per second and the share of bytes it removes."""
+    import paper_2511_03475_amd as cp
+    import workloads as W
+    blocks, turns = W.make_conversation(20251112, turns=40, blocks_per_turn=12, pool_blocks=200,
+                                        lines_per_block=200)
+    total = sum(len(blocks[i]) for ids in turns for i in ids)
+    conv = cp.Conversation(8)
+    t = time.perf_counter()
+    kept = 0
+    for ids in turns:
+        kept += conv.turn(ids, [blocks[i] for i in ids])[1]
+    dt = time.perf_counter() - t
+    conv.close()
+    res = {"workload": f"context_dedup {len(turns)} turns x 12 blocks", "bytes": total, "kept_bytes": kept,
+           "removed_fraction": 1.0 - kept / total, "seconds": dt, "mb_per_s": total / dt / 1e6,
+           "ms_per_turn": dt / len(turns) * 1e3}
+    if cpu:
+        from oracle import context_dedup as OD
+        ref = OD.Conversation(8)
+        t = time.perf_counter()
+        n = 0
+        for ids in turns[:8]:
+            n += sum(len(blocks[i]) for i in ids)
+            ref.turn(ids, [blocks[i] for i in ids])
+        dt = time.perf_counter() - t
+        res["cpu_baseline"] = {"value": n / dt / 1e6, "unit": "MB/s", "kind": "oracle", "cores": 1,
+                               "sample": f"first 8 of {len(turns)} turns ({n} bytes, {dt:.1f} s)"}
+    return res
+
+
 def measure_mfma_ceiling(iters: int = 100000):
     """What the matrix pipe of this device sustains on nothing but back-to-back MFMAs, with
     constant operands and with random-looking ones (the rate depends on operand bit toggling)."""
@@ -404,6 +436,7 @@ def main():
     if not args.no_extra:
         line["context_distance"] = measure_context_distance(cpu=not args.no_cpu)
         line["context_index"] = measure_context_index(cpu=not args.no_cpu)
+        line["context_dedup"] = measure_context_dedup(cpu=not args.no_cpu)
         ceil = measure_mfma_ceiling()
         if line["roofline"]["bound"] == "mfma":
             line["roofline"]["measured_mfma_ceiling_tflops"] = ceil

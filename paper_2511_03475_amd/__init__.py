@@ -1,7 +1,7 @@
 """MI355X (gfx950) extend attention over a paged prefix cache: Python binding of the C ABI."""
 from .binding import (  # noqa: F401
     CP_ERR_LAUNCH, CP_ERR_NULL, CP_ERR_SHAPE, CP_ERR_WORKSPACE, CP_OK, EXPORTS, ContextIndex, CpError, Shape,
-    cp_index_distinct, cp_index_schedule,
+    Conversation, cp_dedup_chunks, cp_dedup_hash, cp_index_distinct, cp_index_schedule,
     cp_context_distance, cp_extend_attention, cp_num_splits, cp_shape, cp_status_string, cp_workspace_bytes,
     cp_probe_mfma, cp_probe_mfma_flops, cp_probe_mfma_sink_floats, cp_write_kv, load_library,
 )

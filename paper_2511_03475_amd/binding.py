@@ -26,7 +26,13 @@ EXPORTS = ("cp_workspace_bytes", "cp_num_splits", "cp_extend_attention", "cp_wri
            "cp_probe_mfma_sink_floats", "cp_probe_mfma_flops",
            "cp_index_distinct", "cp_index_build", "cp_index_free", "cp_index_num_contexts",
            "cp_index_num_nodes", "cp_index_aligned", "cp_index_path", "cp_index_leaf", "cp_index_node",
-           "cp_index_children", "cp_index_search", "cp_index_insert", "cp_index_schedule")
+           "cp_index_children", "cp_index_search", "cp_index_insert", "cp_index_schedule",
+           "cp_dedup_hash", "cp_dedup_chunks", "cp_dedup_create", "cp_dedup_free", "cp_dedup_turn")
+
+
+class cp_dedup_sub(ctypes.Structure):
+    _fields_ = [("block", ctypes.c_int32), ("ref", ctypes.c_int32), ("begin", ctypes.c_int64),
+                ("end", ctypes.c_int64)]
 
 
 class cp_shape(ctypes.Structure):
@@ -109,6 +115,17 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.cp_index_insert.argtypes = [vp, i32p, i32, i32p, i32p, i32, i32p]
     lib.cp_index_schedule.restype = ctypes.c_int
     lib.cp_index_schedule.argtypes = [i32p, i32p, i32, i32, i32p]
+    u8p, i64p = ctypes.POINTER(ctypes.c_uint8), ctypes.POINTER(ctypes.c_int64)
+    lib.cp_dedup_hash.restype = ctypes.c_uint64
+    lib.cp_dedup_hash.argtypes = [u8p, ctypes.c_int64]
+    lib.cp_dedup_chunks.restype = ctypes.c_int
+    lib.cp_dedup_chunks.argtypes = [u8p, ctypes.c_int64, ctypes.c_uint64, i64p, i32, i32p]
+    lib.cp_dedup_create.restype = ctypes.c_int
+    lib.cp_dedup_create.argtypes = [ctypes.c_uint64, ctypes.POINTER(vp)]
+    lib.cp_dedup_free.restype = None
+    lib.cp_dedup_free.argtypes = [vp]
+    lib.cp_dedup_turn.restype = ctypes.c_int
+    lib.cp_dedup_turn.argtypes = [vp, i32p, u8p, i64p, i32, i32p, ctypes.POINTER(cp_dedup_sub), i32, i32p, i64p]
     lib.cp_status_string.restype = ctypes.c_char_p
     lib.cp_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -335,3 +352,62 @@ def cp_index_schedule(paths):
                                                   order.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))),
                  "cp_index_schedule")
     return [int(x) for x in order[:n]]
+
+
+# ---- context de-duplication (host memory only) -----------------------------------------------
+def _u8(data: bytes):
+    buf = (ctypes.c_uint8 * max(len(data), 1)).from_buffer_copy(data if data else b"\0")
+    return buf
+
+
+def cp_dedup_hash(data: bytes) -> int:
+    return int(load_library().cp_dedup_hash(_u8(data), len(data)))
+
+
+def cp_dedup_chunks(data: bytes, modulus: int):
+    """End offsets of the sub-blocks of one block."""
+    cap = data.count(b"\n") + 2
+    ends = (ctypes.c_int64 * cap)()
+    n = ctypes.c_int32(0)
+    _check_index(load_library().cp_dedup_chunks(_u8(data), len(data), int(modulus), ends, cap, ctypes.byref(n)),
+                 "cp_dedup_chunks")
+    return [int(ends[i]) for i in range(n.value)]
+
+
+class Conversation:
+    """Owner of a cp_dedup handle.  turn() is one C call plus argument marshalling."""
+
+    def __init__(self, modulus: int):
+        self._lib = load_library()
+        self._h = ctypes.c_void_p()
+        _check_index(self._lib.cp_dedup_create(int(modulus), ctypes.byref(self._h)), "cp_dedup_create")
+
+    def close(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h.value:
+            self._lib.cp_dedup_free(self._h)
+            self._h = ctypes.c_void_p()
+
+    __del__ = close
+
+    def turn(self, ids, blocks):
+        """Per block ("block", id) or ("subs", [(begin, end, ref), ...]), and the kept bytes."""
+        n = len(ids)
+        data = b"".join(blocks)
+        offsets = (ctypes.c_int64 * (n + 1))()
+        at = 0
+        for i, b in enumerate(blocks):
+            offsets[i] = at
+            at += len(b)
+        offsets[n] = at
+        idv = (ctypes.c_int32 * max(n, 1))(*[int(i) for i in ids])
+        ref = (ctypes.c_int32 * max(n, 1))()
+        cap = data.count(b"\n") + n + 1
+        subs = (cp_dedup_sub * cap)()
+        cnt, kept = ctypes.c_int32(0), ctypes.c_int64(0)
+        _check_index(self._lib.cp_dedup_turn(self._h, idv, _u8(data), offsets, n, ref, subs, cap,
+                                             ctypes.byref(cnt), ctypes.byref(kept)), "cp_dedup_turn")
+        out = [("block", int(ids[i])) if ref[i] else ("subs", []) for i in range(n)]
+        for k in range(cnt.value):
+            s = subs[k]
+            out[s.block][1].append((int(s.begin), int(s.end), int(s.ref)))
+        return out, int(kept.value)

@@ -10,7 +10,8 @@ _ROOT = os.path.dirname(_PKG)
 SOURCES = [os.path.join(_PKG, "csrc", "cp_extend.hip"),
            os.path.join(_PKG, "csrc", "cp_context_distance.hip"),
            os.path.join(_PKG, "csrc", "cp_probe.hip"),
-           os.path.join(_PKG, "csrc", "cp_context_index.cpp")]
+           os.path.join(_PKG, "csrc", "cp_context_index.cpp"),
+           os.path.join(_PKG, "csrc", "cp_context_dedup.cpp")]
 INCLUDE = os.path.join(_ROOT, "include")
 LIB_PATH = os.path.join(_PKG, "libcp_extend.so")
 

@@ -352,3 +352,43 @@ def make_contexts(seed: int, n: int, k, pool_ids: int = 2000, zipf_s: float = 1.
     for i in range(n):
         contexts[i, lens[i]:] = -1
     return contexts, lens
+
+
+def make_conversation(seed: int, turns: int = 6, blocks_per_turn: int = 8, pool_blocks: int = 24,
+                      lines_per_block: int = 40, shared_sections: int = 10,
+                      section_prob: float = 0.35):
+    """Synthetic multi-turn retrieval trace for the de-duplication path: text blocks whose lines
+    are random words, with template sections (runs of 3-8 lines) shared between blocks, and turns
+    that retrieve overlapping sets of block ids (Zipf over the pool).  Stands in for the
+    multi-turn retrieval traces of the paper's datasets.
+
+    Returns (blocks: dict id -> bytes, turns: list of lists of ids).
+    """
+    rng = np.random.default_rng(seed)
+
+    def line() -> bytes:
+        words = ["".join(chr(97 + int(c)) for c in rng.integers(0, 26, size=int(rng.integers(2, 10))))
+                 for _ in range(int(rng.integers(4, 13)))]
+        return (" ".join(words) + "\n").encode()
+
+    sections = [b"".join(line() for _ in range(int(rng.integers(3, 9)))) for _ in range(shared_sections)]
+    blocks = {}
+    for b in range(pool_blocks):
+        parts, n = [], 0
+        while n < lines_per_block:
+            if shared_sections and rng.random() < section_prob / 4:
+                s = sections[int(rng.integers(0, shared_sections))]
+                parts.append(s)
+                n += s.count(b"\n")
+            else:
+                parts.append(line())
+                n += 1
+        text = b"".join(parts)
+        if b % 3 == 0:
+            text = text[:-1]                 # some blocks end without a newline
+        blocks[b] = text
+    w = (np.arange(pool_blocks, dtype=np.float64) + 1.0) ** -1.1
+    w /= w.sum()
+    seq = [[int(i) for i in rng.choice(pool_blocks, size=min(blocks_per_turn, pool_blocks), replace=False, p=w)]
+           for _ in range(turns)]
+    return blocks, seq
