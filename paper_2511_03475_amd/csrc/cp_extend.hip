@@ -115,9 +115,8 @@ struct TileRegs {
 };
 
 // LDS: four K buffers and four V buffers of one 64-key tile (16 KiB) each, tile t in buffer
-// t % 4.  The two groups of four wavefronts run half an iteration apart (see the main loop), a
-// tile is written two iterations before its first use, and V(t) is still read one iteration
-// after K(t), which together need four buffers of each.
+// t % 4.  A tile is written two iterations before its first use and V(t) is still read one
+// iteration after K(t); with one barrier per iteration that needs four buffers of each.
 // Rows are padded instead of swizzled so that every LDS read address is a per-lane base plus
 // an immediate: K rows have a pitch of 272 bytes (16 consecutive rows at the same column fall
 // into 16 different 16-byte bank groups), V rows a pitch of 320 bytes (the four consecutive

@@ -295,3 +295,38 @@ def test_decode_kernel_finds_a_needle_in_a_long_prefix(H):
     _check(got, want, "decode needle")
     v = bf16_bits_to_f32(w.kv_pages[page, 1, 0, slot, :]).astype(np.float64)
     assert np.abs(bf16_bits_to_f32(got)[0, 0].astype(np.float64) - v).max() < 5e-2
+
+
+def _random_shape(rng):
+    """One small random case: ragged batch, any GQA shape, lengths that straddle pages, key
+    tiles, row tiles and the sizes at which the library changes kernel or head packing."""
+    B = int(rng.integers(1, 6))
+    Hkv = int(rng.choice([1, 2, 3]))
+    G = int(rng.choice([1, 2, 4, 6, 8]))
+    regime = rng.choice(["decode", "short", "mixed", "long"])
+    hiE = {"decode": 9, "short": 70, "mixed": 300, "long": 520}[regime]
+    E = rng.integers(0 if regime == "mixed" else 1, hiE, size=B)
+    P = rng.integers(0, 900, size=B)
+    P[rng.random(B) < 0.2] = 0
+    snap = rng.random(B) < 0.3        # some lengths exactly on page / tile boundaries
+    P[snap] = (P[snap] // 64) * 64
+    if E.sum() == 0:
+        E[0] = 1
+    return B, G, Hkv, [int(x) for x in P], [int(x) for x in E]
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_attention_and_cache_write(H, seed):
+    rng = np.random.default_rng(7700 + seed)
+    B, G, Hkv, P, E = _random_shape(rng)
+    w = W.make_uniform("fuzz", 7700 + seed, B, G * Hkv, Hkv, P, E, extra_table_cols=int(rng.integers(0, 3)))
+    want = oracle.attention_of(w)
+    what = f"seed={seed} B={B} G={G} Hkv={Hkv} P={P} E={E}"
+    _check(H.gpu_attention(w), want, what + " auto")
+    ns = int(rng.integers(1, 6))
+    _check(H.gpu_attention(w, num_splits=ns), want, what + f" splits={ns}")
+    case = H.DeviceCase(w)
+    case.write_kv()
+    np.testing.assert_array_equal(
+        case.pool_bits(),
+        oracle.write_kv(w.k_new, w.v_new, w.kv_pages, w.block_table, w.prefix_lens, w.extend_lens))
