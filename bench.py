@@ -148,9 +148,19 @@ class Runner:
         if ev is not None:
             ev[1].record(stream)
 
-    def run(self, steps: int, warmup: int):
+    def run(self, steps: int, warmup: int, settle_ms: float = 0.0):
         torch = self.torch
         stream = torch.cuda.current_stream()
+        if settle_ms > 0:
+            # The device clock dips a few ms after load begins and takes ~50 ms to reach its
+            # steady value; short workloads would otherwise be timed inside that transient.
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            self.step(stream)
+            torch.cuda.synchronize()
+            one = max((time.perf_counter() - t0) * 1e3, 1e-3)
+            for _ in range(min(2000, int(settle_ms / one) + 1)):
+                self.step(stream)
         for _ in range(warmup):
             self.step(stream)
         events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
@@ -165,12 +175,15 @@ class Runner:
         return (t1 - t0) * 1e3 / steps, float(np.mean(attn_ms)), float(np.min(attn_ms))
 
 
+SETTLE_MS = 100.0   # untimed run-in before the warm-up steps, see Runner.run
+
+
 def measure(name: str, steps: int, warmup: int):
     t = time.perf_counter()
     w = _workload(name)
     gen_s = time.perf_counter() - t
     r = Runner(w)
-    ms_step, attn_ms, attn_min = r.run(steps, warmup)
+    ms_step, attn_ms, attn_min = r.run(steps, warmup, SETTLE_MS)
     flops = w.flops()
     res = {
         "workload": name, "batch": w.batch, "q_heads": w.num_q_heads, "kv_heads": w.num_kv_heads,
@@ -345,7 +358,8 @@ def measure_mfma_ceiling(iters: int = 100000):
     stream = torch.cuda.current_stream()
     out = {}
     for name, rnd in (("constant_operands", False), ("random_operands", True)):
-        cp.cp_probe_mfma(rnd, 1000, sink, stream)
+        for _ in range(4):   # ~100 ms of the same load first: steady clock, as for the workloads
+            cp.cp_probe_mfma(rnd, iters, sink, stream)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         a.record(stream)
@@ -364,9 +378,12 @@ def main():
     ap.add_argument("--workload", default="long_context_32k")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--settle-ms", type=float, default=SETTLE_MS,
+                    help="untimed run-in of each workload before its warm-up steps (clock transient)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for HBM counters)")
     args = ap.parse_args()
+    globals()["SETTLE_MS"] = args.settle_ms
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only; use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -416,7 +433,8 @@ def main():
     line = {
         "metric": "extend-attention TFLOP/s and % of bf16 MFMA peak at 32k/128k ctx",
         "value": head["tflops_step"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True,
+        "warmup": args.warmup, "clock_settle_ms": args.settle_ms, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "batch": head["batch"], "q_heads": head["q_heads"],
                    "kv_heads": head["kv_heads"], "head_dim": 128, "page_size": 16,
