@@ -343,6 +343,17 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
                 s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), qf[kk], s[b], 0, 0, 0);
             }
         }
+        // Issue order: kFragsAhead fragment reads first, then one read behind every MFMA, so
+        // that an operand is requested kFragsAhead MFMAs before it is used (left alone, the
+        // scheduler reads two fragments and waits for them at once).
+        constexpr int kFragsAhead = 8;
+        __builtin_amdgcn_sched_group_barrier(0x100, kFragsAhead, 0);
+#pragma unroll
+        for (int i = 0; i < 8 * kNKB - kFragsAhead; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, kFragsAhead, 0);
     };
     // O^T += V^T P^T for the tile in V buffer vbuf: 4 d blocks x steps of 16 keys.
     auto pv_tile = [&](int vbuf, const PTile &pb) {
@@ -360,6 +371,16 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
                 o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pb[ks], o[db], 0, 0, 0);
             }
         }
+        // Same for the V fragments (two transposing reads each), four MFMAs ahead; the
+        // exponentials of the next tile fill the gaps wherever the scheduler puts them.
+        constexpr int kFragsAhead = 4;
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * kFragsAhead, 0);
+#pragma unroll
+        for (int i = 0; i < 8 * kNKB - kFragsAhead; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, kFragsAhead, 0);
     };
     // Masks the keys of a boundary tile that the lane's row must not see.  Accumulator element
     // v of block b is key b*32 + 8*(v/4) + 4*h + v%4 of the tile.
@@ -488,7 +509,44 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     };
     int it = 1;
     if (have_prev) {
-        // a single call site, so that the accumulators stay in the same registers throughout
+        // Steady state over the inside of the prefix: tile kt needs no mask and tile kt + 2 is
+        // a full prefix tile, so the step has no case distinctions, and the block-table
+        // entries of a tile are fetched one iteration before its loads are issued (the
+        // general step spends ~500 of ~4200 cycles per tile between the barrier and its
+        // first MFMA on tile kinds, table lookups and addresses, with the matrix pipe idle).
+        const int fast_end = min(n_it - 2, P / kBN - 2 - kt_begin);
+        if (it < fast_end) {
+            const int tsel = wave >> 2;
+            const int last_entry = p.max_pages - 1;
+            auto entry = [&](int kt, int i) {
+                return (uint32_t)table[min(kt * (kBN / kPS) + 2 * i + tsel, last_entry)];
+            };
+            uint32_t pg0 = entry(kt_begin + it + 2, 0), pg1 = entry(kt_begin + it + 2, 1);
+            for (; it < fast_end; ++it) {
+                const int buf = it & 3;
+                const gptr b0 = pages_head + (uint64_t)pg0 * page_bytes;
+                const gptr b1 = pages_head + (uint64_t)pg1 * page_bytes;
+                tr.k[0] = *(const __attribute__((address_space(1))) u32x4 *)(b0 + pg_lane_k);
+                tr.v[0] = *(const __attribute__((address_space(1))) u32x4 *)(b0 + pg_lane_v);
+                tr.k[1] = *(const __attribute__((address_space(1))) u32x4 *)(b1 + pg_lane_k);
+                tr.v[1] = *(const __attribute__((address_space(1))) u32x4 *)(b1 + pg_lane_v);
+                pg0 = entry(kt_begin + it + 3, 0);
+                pg1 = entry(kt_begin + it + 3, 1);
+                __builtin_amdgcn_sched_group_barrier(0x020, 4, 0); // the tile loads go first
+                STile s;
+                qk_tile(buf, s);
+                float psum = exp_tile(s, pb_b, (m_ref == -INFINITY) ? 0.f : m_ref);
+                pv_tile((buf + 3) & 3, pb_a);
+                if (__builtin_amdgcn_ballot_w64(!(psum < kStale) || m_ref == -INFINITY) != 0)
+                    psum = redo_tile(s, pb_b);
+                l_run += psum;
+                store_tile(tr, (buf + 2) & 3);
+                __syncthreads();
+#pragma unroll
+                for (int t = 0; t < 2 * kNKB; ++t) pb_a[t] = pb_b[t];
+            }
+        }
+        // the general step: one call site, so that the accumulators stay in the same registers
         for (; it < n_it && !skipped(kt_begin + it); ++it) {
             tile_step(it, pb_b, pb_a);
 #pragma unroll
