@@ -356,7 +356,7 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
         __builtin_amdgcn_sched_group_barrier(0x008, kFragsAhead, 0);
     };
     // O^T += V^T P^T for the tile in V buffer vbuf: 4 d blocks x steps of 16 keys.
-    auto pv_tile = [&](int vbuf, const PTile &pb) {
+    auto pv_tile = [&](int vbuf, const PTile &pb, auto with_store) {
         const char *vb = lds_v + vbuf * kTileBytesV + v_lane;
 #pragma unroll
         for (int ks = 0; ks < 2 * kNKB; ++ks) { // keys ks*16 .. ks*16+15
@@ -371,16 +371,21 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
                 o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pb[ks], o[db], 0, 0, 0);
             }
         }
-        // Same for the V fragments (two transposing reads each), four MFMAs ahead; the
-        // exponentials of the next tile fill the gaps wherever the scheduler puts them.
+        // Same for the V fragments (two transposing reads each), four MFMAs ahead, with two of
+        // the next tile's 32 exponentials behind every MFMA where the caller has them in the
+        // same block (the other VALU work follows its exponentials by dependency).
         constexpr int kFragsAhead = 4;
+        constexpr bool kStore = decltype(with_store)::value;
         __builtin_amdgcn_sched_group_barrier(0x100, 2 * kFragsAhead, 0);
 #pragma unroll
-        for (int i = 0; i < 8 * kNKB - kFragsAhead; ++i) {
+        for (int i = 0; i < 8 * kNKB; ++i) {
+            // the caller's four LDS writes of the next tile go between the last MFMAs, where
+            // their latency is covered, instead of in front of the barrier
+            if (kStore && i == 8 * kNKB - 2) __builtin_amdgcn_sched_group_barrier(0x200, 4, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            if (i < 8 * kNKB - kFragsAhead) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, kFragsAhead, 0);
     };
     // Masks the keys of a boundary tile that the lane's row must not see.  Accumulator element
     // v of block b is key b*32 + 8*(v/4) + 4*h + v%4 of the tile.
@@ -500,7 +505,7 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
         masked_qk(kt, buf, s);
         // one basic block: the exponentials (VALU) interleave with P V (MFMA)
         float psum = exp_tile(s, pb_cur, (m_ref == -INFINITY) ? 0.f : m_ref);
-        pv_tile((buf + 3) & 3, pb_prev);
+        pv_tile((buf + 3) & 3, pb_prev, std::false_type{});
         if (__builtin_amdgcn_ballot_w64(!(psum < kStale) || m_ref == -INFINITY) != 0)
             psum = redo_tile(s, pb_cur);
         l_run += psum;
@@ -536,11 +541,11 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
                 STile s;
                 qk_tile(buf, s);
                 float psum = exp_tile(s, pb_b, (m_ref == -INFINITY) ? 0.f : m_ref);
-                pv_tile((buf + 3) & 3, pb_a);
+                pv_tile((buf + 3) & 3, pb_a, std::true_type{});
+                store_tile(tr, (buf + 2) & 3);
                 if (__builtin_amdgcn_ballot_w64(!(psum < kStale) || m_ref == -INFINITY) != 0)
                     psum = redo_tile(s, pb_b);
                 l_run += psum;
-                store_tile(tr, (buf + 2) & 3);
                 __syncthreads();
 #pragma unroll
                 for (int t = 0; t < 2 * kNKB; ++t) pb_a[t] = pb_b[t];
@@ -553,7 +558,7 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
             for (int t = 0; t < 2 * kNKB; ++t) pb_a[t] = pb_b[t];
         }
         // P V of the last tile this wavefront computed (tile it - 1)
-        pv_tile((it - 1) & 3, pb_a);
+        pv_tile((it - 1) & 3, pb_a, std::false_type{});
     }
     // remaining tiles are invisible to this wavefront: only take part in the cooperative loads
     for (; it < n_it; ++it) {
