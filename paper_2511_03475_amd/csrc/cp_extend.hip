@@ -514,12 +514,20 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     };
     int it = 1;
     if (have_prev) {
-        // Steady state over the inside of the prefix: tile kt needs no mask and tile kt + 2 is
-        // a full prefix tile, so the step has no case distinctions, and the block-table
-        // entries of a tile are fetched one iteration before its loads are issued (the
-        // general step spends ~500 of ~4200 cycles per tile between the barrier and its
-        // first MFMA on tile kinds, table lookups and addresses, with the matrix pipe idle).
-        const int fast_end = min(n_it - 2, P / kBN - 2 - kt_begin);
+        // Steady state: while tile kt needs no mask for this wavefront and tile kt + 2 is a
+        // full tile (inside the prefix, or suffix rows below the diagonal), the step has no
+        // case distinctions, and the block-table entries of a tile are fetched one iteration
+        // before its loads are issued (the general step spends ~500 of ~4200 cycles per tile
+        // between the barrier and its first MFMA on tile kinds, table lookups and addresses,
+        // with the matrix pipe idle).
+        int fast_end;
+        if (P % kBN == 0) {
+            const int last_unmasked = np_tiles + (wave_row0 >= kBN - 1 ? (wave_row0 - (kBN - 1)) / kBN : -1);
+            const int last_full = np_tiles + E / kBN - 1;
+            fast_end = min(min(last_unmasked + 1, last_full - 1), kt_end - 2) - kt_begin;
+        } else {
+            fast_end = min(n_it - 2, P / kBN - 2 - kt_begin);
+        }
         if (it < fast_end) {
             const int tsel = wave >> 2;
             const int last_entry = p.max_pages - 1;
@@ -529,12 +537,26 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
             uint32_t pg0 = entry(kt_begin + it + 2, 0), pg1 = entry(kt_begin + it + 2, 1);
             for (; it < fast_end; ++it) {
                 const int buf = it & 3;
-                const gptr b0 = pages_head + (uint64_t)pg0 * page_bytes;
-                const gptr b1 = pages_head + (uint64_t)pg1 * page_bytes;
-                tr.k[0] = *(const __attribute__((address_space(1))) u32x4 *)(b0 + pg_lane_k);
-                tr.v[0] = *(const __attribute__((address_space(1))) u32x4 *)(b0 + pg_lane_v);
-                tr.k[1] = *(const __attribute__((address_space(1))) u32x4 *)(b1 + pg_lane_k);
-                tr.v[1] = *(const __attribute__((address_space(1))) u32x4 *)(b1 + pg_lane_v);
+                const int kt2 = kt_begin + it + 2;
+                gptr k0, v0, k1, v1;
+                if (kt2 < np_tiles) {
+                    const gptr b0 = pages_head + (uint64_t)pg0 * page_bytes;
+                    const gptr b1 = pages_head + (uint64_t)pg1 * page_bytes;
+                    k0 = b0 + pg_lane_k;
+                    v0 = b0 + pg_lane_v;
+                    k1 = b1 + pg_lane_k;
+                    v1 = b1 + pg_lane_v;
+                } else {
+                    const int64_t off = (int64_t)(kt2 - np_tiles) * kBN * row_bytes + sfx_lane;
+                    k0 = knew_head + off;
+                    v0 = vnew_head + off;
+                    k1 = k0 + (int64_t)kLoadRows * row_bytes;
+                    v1 = v0 + (int64_t)kLoadRows * row_bytes;
+                }
+                tr.k[0] = *(const __attribute__((address_space(1))) u32x4 *)k0;
+                tr.v[0] = *(const __attribute__((address_space(1))) u32x4 *)v0;
+                tr.k[1] = *(const __attribute__((address_space(1))) u32x4 *)k1;
+                tr.v[1] = *(const __attribute__((address_space(1))) u32x4 *)v1;
                 pg0 = entry(kt_begin + it + 3, 0);
                 pg1 = entry(kt_begin + it + 3, 1);
                 __builtin_amdgcn_sched_group_barrier(0x020, 4, 0); // the tile loads go first
