@@ -303,10 +303,10 @@ def _random_shape(rng):
     B = int(rng.integers(1, 6))
     Hkv = int(rng.choice([1, 2, 3]))
     G = int(rng.choice([1, 2, 4, 6, 8]))
-    regime = rng.choice(["decode", "short", "mixed", "long"])
-    hiE = {"decode": 9, "short": 70, "mixed": 300, "long": 520}[regime]
+    regime = rng.choice(["decode", "short", "mixed", "long", "long_prefix"])
+    hiE = {"decode": 9, "short": 70, "mixed": 300, "long": 520, "long_prefix": 200}[regime]
     E = rng.integers(0 if regime == "mixed" else 1, hiE, size=B)
-    P = rng.integers(0, 900, size=B)
+    P = rng.integers(0, 3000 if regime == "long_prefix" else 900, size=B)  # long: the steady-state loop
     P[rng.random(B) < 0.2] = 0
     snap = rng.random(B) < 0.3        # some lengths exactly on page / tile boundaries
     P[snap] = (P[snap] // 64) * 64
@@ -315,7 +315,7 @@ def _random_shape(rng):
     return B, G, Hkv, [int(x) for x in P], [int(x) for x in E]
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", range(24))
 def test_random_shapes_attention_and_cache_write(H, seed):
     rng = np.random.default_rng(7700 + seed)
     B, G, Hkv, P, E = _random_shape(rng)
