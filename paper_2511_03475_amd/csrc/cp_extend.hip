@@ -530,7 +530,7 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
         }
         if (it < fast_end) {
             const int tsel = wave >> 2;
-            const int last_entry = p.max_pages - 1;
+            const int last_entry = (P + E + kPS - 1) / kPS - 1; // last page of the request: nothing beyond it is read
             auto entry = [&](int kt, int i) {
                 return (uint32_t)table[min(kt * (kBN / kPS) + 2 * i + tsel, last_entry)];
             };
