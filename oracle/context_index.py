@@ -7,8 +7,7 @@ TEST INFRASTRUCTURE ONLY: imported by the tests and by the CPU-baseline leg of t
 The C++ library never imports this module and this module imports nothing from it.  Everything
 here is written for reading, not for speed: lists, sets, explicit loops, cubic-time clustering.
 
-Where the paper leaves a choice open, the reading taken is stated where it is used; the same
-list is in the design notes of the repository.
+Where the paper leaves a choice open, the reading taken is stated where it is used.
 """
 from __future__ import annotations
 
