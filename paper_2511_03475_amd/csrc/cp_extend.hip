@@ -910,7 +910,10 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_attn_kernel(const At
     }
 }
 
-// One workgroup copies 16 consecutive packed rows; one thread moves 16 bytes at a time.
+// One workgroup copies 16 consecutive packed rows.  Its first wavefront finds the request, the
+// page and the slot of every row, 64 requests at a time (a prefix sum of extend_lens across the
+// lanes; a sequential scan costs one dependent load per request, which made a 32-row call take
+// 30 us); then thread (row, 16-byte chunk) copies the row's K and V for every KV head.
 constexpr int kWriteRows = 16;
 __global__ __launch_bounds__(256) void write_kv_kernel(const uint16_t *__restrict__ k_new,
                                                        const uint16_t *__restrict__ v_new,
@@ -920,35 +923,70 @@ __global__ __launch_bounds__(256) void write_kv_kernel(const uint16_t *__restric
                                                        const int32_t *__restrict__ extend_lens,
                                                        int batch, int Hkv, int max_pages, int T)
 {
+    __shared__ int64_t s_page[kWriteRows]; // physical page of the row's token, -1: no such row
+    __shared__ int s_slot[kWriteRows];     // its slot inside the page
     const int row0 = blockIdx.x * kWriteRows;
-    // request of the first row of the block
-    int r = 0, cu = 0;
-    while (r < batch && row0 >= cu + extend_lens[r]) {
-        cu += extend_lens[r];
-        ++r;
-    }
-    const int chunks_per_row = Hkv * 16; // 16-byte chunks of one row of k_new (or v_new)
-    const int total = kWriteRows * 2 * chunks_per_row;
-    for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
-        const int lr = idx / (2 * chunks_per_row);
-        int rest = idx - lr * 2 * chunks_per_row;
-        const int which = rest / chunks_per_row;
-        rest -= which * chunks_per_row;
-        const int g = rest >> 4;
-        const int ch = rest & 15;
-        const int row = row0 + lr;
-        if (row >= T) continue;
-        int rr = r, cc = cu;
-        while (rr < batch && row >= cc + extend_lens[rr]) {
-            cc += extend_lens[rr];
-            ++rr;
+    const int lane = threadIdx.x & 63;
+    if (threadIdx.x < 64) {
+        int req = -1, off = 0; // lane i < 16: owner of row row0 + i and the row's index inside it
+        int cu = 0;            // rows of the requests before `base`
+        for (int base = 0; base < batch; base += 64) {
+            const int rr = base + lane;
+            const int e = rr < batch ? extend_lens[rr] : 0;
+            const int incl = wave_inclusive_scan(e, lane);
+            const int total = __builtin_amdgcn_readlane(incl, 63);
+#pragma unroll
+            for (int i = 0; i < kWriteRows; ++i) {
+                const int t = row0 + i - cu; // the row's index among the rows of this group of requests
+                if (t >= 0 && t < total) {
+                    const int first = __builtin_ctzll(__builtin_amdgcn_ballot_w64(incl > t));
+                    const int before = __builtin_amdgcn_readlane(incl - e, first);
+                    if (lane == i) {
+                        req = base + first;
+                        off = t - before;
+                    }
+                }
+            }
+            if (row0 + kWriteRows - 1 - cu < total) break;
+            cu += total;
         }
-        if (rr >= batch) continue;
-        const int tok = prefix_lens[rr] + (row - cc);
-        const int64_t page = block_table[(int64_t)rr * max_pages + (tok >> 4)];
-        const uint16_t *src = (which ? v_new : k_new) + ((int64_t)row * Hkv + g) * kD + ch * 8;
-        uint16_t *dst = kv_pages + ((((page * 2 + which) * Hkv + g) * kPS + (tok & 15)) * (int64_t)kD + ch * 8);
-        *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+        if (lane < kWriteRows) {
+            int64_t page = -1;
+            int slot = 0;
+            if (req >= 0 && row0 + lane < T) {
+                const int tok = prefix_lens[req] + off;
+                page = block_table[(int64_t)req * max_pages + (tok >> 4)];
+                slot = tok & 15;
+            }
+            s_page[lane] = page;
+            s_slot[lane] = slot;
+        }
+    }
+    __syncthreads();
+    const int lr = threadIdx.x >> 4; // row of the block
+    const int ch = threadIdx.x & 15; // 16-byte chunk of a 256-byte head row
+    const int64_t page = s_page[lr];
+    if (page < 0) return;
+    const int64_t row = row0 + lr;
+    const uint16_t *ksrc = k_new + row * Hkv * kD + ch * 8;
+    const uint16_t *vsrc = v_new + row * Hkv * kD + ch * 8;
+    uint16_t *kdst = kv_pages + ((page * 2 * Hkv) * kPS + s_slot[lr]) * (int64_t)kD + ch * 8;
+    uint16_t *vdst = kdst + (int64_t)Hkv * kPS * kD;
+    const int64_t head_pitch = (int64_t)kPS * kD; // one KV head's slab inside a page
+    int g = 0;
+    for (; g + 2 <= Hkv; g += 2) { // four independent copies in flight
+        const uint4 k0 = *reinterpret_cast<const uint4 *>(ksrc + (int64_t)g * kD);
+        const uint4 k1 = *reinterpret_cast<const uint4 *>(ksrc + (int64_t)(g + 1) * kD);
+        const uint4 v0 = *reinterpret_cast<const uint4 *>(vsrc + (int64_t)g * kD);
+        const uint4 v1 = *reinterpret_cast<const uint4 *>(vsrc + (int64_t)(g + 1) * kD);
+        *reinterpret_cast<uint4 *>(kdst + g * head_pitch) = k0;
+        *reinterpret_cast<uint4 *>(kdst + (g + 1) * head_pitch) = k1;
+        *reinterpret_cast<uint4 *>(vdst + g * head_pitch) = v0;
+        *reinterpret_cast<uint4 *>(vdst + (g + 1) * head_pitch) = v1;
+    }
+    for (; g < Hkv; ++g) {
+        *reinterpret_cast<uint4 *>(kdst + g * head_pitch) = *reinterpret_cast<const uint4 *>(ksrc + (int64_t)g * kD);
+        *reinterpret_cast<uint4 *>(vdst + g * head_pitch) = *reinterpret_cast<const uint4 *>(vsrc + (int64_t)g * kD);
     }
 }
 
