@@ -28,9 +28,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # WRITE_SIZE x 1.0, scale factors from a 1 GiB device copy in the same run), valid only for the
 # kernel source they were taken with: reported as null as soon as that source changes.
 TRAFFIC = {
-    "source_sha256_16": "8e77ee8e16e15807",
-    "long_context_32k": (2130356 * 2.0 + 524289) * 1024.0,      # extend_attn_kernel
-    "decode_b32_p10k": (656151 * 2.0 + 4160) * 1024.0,          # decode_attn_kernel
+    "source_sha256_16": "345b83203334e8fd",
+    "long_context_32k": (2130348 * 2.0 + 524288) * 1024.0,      # extend_attn_kernel
+    "decode_b32_p10k": (656159 * 2.0 + 4161) * 1024.0,          # decode_attn_kernel
 }
 
 

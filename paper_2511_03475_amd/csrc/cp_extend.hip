@@ -733,8 +733,12 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_attn_kernel(const At
     const int E = p.extend_lens[r];
     if (E <= 0) return;
     const int P = p.prefix_lens[r];
+    // packed row of the request's first token: sum of the earlier extend lengths, 64 per step
     int cu = 0;
-    for (int i = 0; i < r; ++i) cu += p.extend_lens[i];
+    for (int base = 0; base < r; base += 64) cu += base + lane < r ? p.extend_lens[base + lane] : 0;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) cu += __shfl_xor(cu, off, 64);
+    cu = __builtin_amdgcn_readfirstlane(cu);
     const int N = P + E;
     const int nblk = (N + 31) >> 5;
     const int per = (nblk + p.nsplit - 1) / p.nsplit;

@@ -297,6 +297,26 @@ def test_decode_kernel_finds_a_needle_in_a_long_prefix(H):
     assert np.abs(bf16_bits_to_f32(got)[0, 0].astype(np.float64) - v).max() < 5e-2
 
 
+@pytest.mark.parametrize("max_e", [2, 40])
+def test_large_batches_with_empty_requests(H, max_e):
+    """More requests than one lookup step of 64 covers, many of them without extend tokens:
+    every kernel finds the owner of a row or work unit by prefix sums over extend_lens
+    (max_e = 2: decode-shaped kernel, max_e = 40: row-tiled kernel; cache write in both)."""
+    rng = np.random.default_rng(4242 + max_e)
+    B = 200
+    E = rng.integers(0, max_e + 1, size=B)
+    E[rng.random(B) < 0.3] = 0
+    E[-1] = max_e
+    P = rng.integers(0, 70, size=B)
+    w = W.make_uniform("many", 4242 + max_e, B, 4, 2, [int(x) for x in P], [int(x) for x in E])
+    _check(H.gpu_attention(w), oracle.attention_of(w), f"B={B} max_e={max_e}")
+    case = H.DeviceCase(w)
+    case.write_kv()
+    np.testing.assert_array_equal(
+        case.pool_bits(),
+        oracle.write_kv(w.k_new, w.v_new, w.kv_pages, w.block_table, w.prefix_lens, w.extend_lens))
+
+
 def _random_shape(rng):
     """One small random case: ragged batch, any GQA shape, lengths that straddle pages, key
     tiles, row tiles and the sizes at which the library changes kernel or head packing."""
