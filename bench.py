@@ -404,6 +404,10 @@ def main():
         del a, b
         torch.cuda.empty_cache()
 
+    if args.workload == "context_distance":   # the distance kernel alone (for profiling it)
+        print(json.dumps(measure_context_distance(steps=args.steps, cpu=not args.no_cpu)))
+        return
+
     w, r, head = measure(args.workload, args.steps, args.warmup)
     cpu = None if args.no_cpu else cpu_baseline(w)
     del r
