@@ -74,6 +74,9 @@ def _workload(name: str):
         "decode_b32_p10k": lambda: W.make_uniform("decode_b32_p10k", W.BASE_SEED + 7, 32, 32, 8, 10240, 1),
         "decode_b32_p10k_e16": lambda: W.make_uniform("decode_b32_p10k_e16", W.BASE_SEED + 8, 32, 32, 8, 10240, 16),
         "decode_b1_p128k": lambda: W.make_uniform("decode_b1_p128k", W.BASE_SEED + 9, 1, 32, 8, 131072, 1),
+        # one 2048-token chunk of a chunked prefill over 16k tokens already in the cache
+        "chunked_prefill_b8_p16k_e2k": lambda: W.make_uniform("chunked_prefill_b8_p16k_e2k", W.BASE_SEED + 10, 8, 32, 8,
+                                                              16384, 2048),
         "rag_zipf_as_retrieved": lambda: W.rag_batch_from_blocks("rag_zipf_as_retrieved", W.BASE_SEED + 3,
                                                                  W.rag_zipf_picks()),
     }
@@ -417,6 +420,7 @@ def main():
     if not args.no_extra:
         for name in ("tiny_extend", "rag_fixed", "rag_zipf", "rag_zipf_as_retrieved", "rag_zipf_context_index",
                      "long_context_32k", "ctx128k_zero_reuse", "ctx128k_reuse", "short_extend_probe",
+                     "chunked_prefill_b8_p16k_e2k",
                      "decode_b32_p10k", "decode_b32_p10k_e16", "decode_b1_p128k"):
             if name == args.workload:
                 extra.append({k: head[k] for k in head})

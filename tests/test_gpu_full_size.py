@@ -66,6 +66,18 @@ def test_config5_128k_zero_reuse_and_reuse_sampled(H):
     _sampled(H, wb, rows, "config5b 87.5% reuse")
 
 
+def test_chunked_prefill_and_decode_workloads_sampled(H):
+    """The other shapes bench.py times: one 2048-token chunk over 16k cached tokens, and the
+    decode batch (32 requests x 10240 cached tokens, one new token each; decode-shaped kernel)."""
+    w = W.make_uniform("chunked_prefill_b8_p16k_e2k", W.BASE_SEED + 10, 8, 32, 8, 16384, 2048)
+    rows = W.sample_rows(w, 10, q_block=512, edge=2, seams=2)
+    _sampled(H, w, rows, "chunked prefill")
+    del w
+    w = W.make_uniform("decode_b32_p10k", W.BASE_SEED + 7, 32, 32, 8, 10240, 1)
+    got = H.gpu_attention(w)
+    _check(got, oracle.attention_of(w), "decode batch, all 32 rows")
+
+
 def test_needle_hits_every_page_at_128k(H):
     """P=114688, E=16384, 32/8 heads: each of the 8192 pages is the target of one query row."""
     P, E, PS = 114688, 16384, 16
