@@ -24,13 +24,18 @@
  *
  * Ownership: the caller owns every buffer and the stream.  The library allocates no device
  * memory, never synchronises and never changes the current device; all work is enqueued on
- * `stream` (a hipStream_t passed as void*; NULL is the default stream).  All pointers must be
- * 16-byte aligned.
+ * `stream` (a hipStream_t passed as void*; NULL is the default stream).  q, out, k_new, v_new
+ * and kv_pages must be 16-byte aligned (the kernels move them in 16-byte pieces), the int32
+ * arrays 4-byte aligned; a pointer that is not is refused with CP_ERR_ALIGN.
  *
  * Errors: every entry point validates its host-visible arguments before any launch and
  * returns CP_OK or a negative code; nothing is enqueued when a code other than CP_OK or
  * CP_ERR_LAUNCH is returned.  Device-side contents (block_table entries inside
- * [0, num_pages), device lengths equal to the host copies) are not validated.
+ * [0, num_pages), device lengths equal to the host copies) are not validated by default,
+ * because that needs a wait for the stream: cp_check_tables does it on request, and in debug
+ * mode (cp_set_debug_validate, the environment variable CP_DEBUG_VALIDATE=1, or a library built
+ * with -DCP_DEBUG_VALIDATE) cp_extend_attention and cp_write_kv run the same check first and
+ * launch nothing when it fails.
  */
 #ifndef CP_EXTEND_H
 #define CP_EXTEND_H
@@ -47,7 +52,10 @@ enum {
     CP_ERR_NULL = -1,      /* a required pointer is NULL */
     CP_ERR_SHAPE = -2,     /* unsupported or inconsistent shape (see cp_shape) */
     CP_ERR_WORKSPACE = -3, /* workspace missing, too small or misaligned */
-    CP_ERR_LAUNCH = -4     /* the HIP runtime reported a launch error */
+    CP_ERR_LAUNCH = -4,    /* the HIP runtime reported an error */
+    CP_ERR_ALIGN = -5,     /* a device pointer is not aligned as required */
+    CP_ERR_TABLE = -6,     /* check: a block_table entry in use lies outside [0, num_pages) */
+    CP_ERR_LENGTHS = -7    /* check: device prefix_lens / extend_lens differ from the host copies */
 };
 
 typedef struct cp_shape {
@@ -112,6 +120,24 @@ int cp_extend_attention(const void *q, const void *k_new, const void *v_new,
 int cp_write_kv(const void *k_new, const void *v_new, void *kv_pages,
                 const int32_t *block_table, const int32_t *prefix_lens,
                 const int32_t *extend_lens, void *stream, const cp_shape *shape);
+
+/*
+ * Check of the device-side contents that the two calls above trust (the setting is the same:
+ * paper, Section 2.1, a prefix cache maps prompts to KV-block identifiers, and a wrong
+ * identifier would make the kernels read or write outside the page pool).  Copies the device
+ * prefix_lens / extend_lens to the host and compares them with the host copies in *shape
+ * (CP_ERR_LENGTHS), then runs a small kernel that reads block_table[r][i] for every slot in use,
+ * i < ceil((P_r + E_r) / PS), and reports the first entry outside [0, num_pages) (CP_ERR_TABLE);
+ * no page is dereferenced.  WAITS for `stream`; meant for tests and debugging.
+ * info: optional HOST int32[3]; on CP_ERR_TABLE {request, slot, entry}, on CP_ERR_LENGTHS
+ * {request, device P_r, device E_r}, otherwise -1.
+ */
+int cp_check_tables(const int32_t *block_table, const int32_t *prefix_lens,
+                    const int32_t *extend_lens, void *stream, const cp_shape *shape,
+                    int32_t *info);
+
+/* Debug mode on (non-zero) or off for this process: see "Errors" at the top. */
+void cp_set_debug_validate(int on);
 
 /* Static, human-readable text for a status code. */
 const char *cp_status_string(int status);

@@ -20,9 +20,12 @@ CP_ERR_NULL = -1
 CP_ERR_SHAPE = -2
 CP_ERR_WORKSPACE = -3
 CP_ERR_LAUNCH = -4
+CP_ERR_ALIGN = -5
+CP_ERR_TABLE = -6
+CP_ERR_LENGTHS = -7
 
 EXPORTS = ("cp_workspace_bytes", "cp_num_splits", "cp_extend_attention", "cp_write_kv",
-           "cp_status_string", "cp_context_distance", "cp_probe_mfma",
+           "cp_status_string", "cp_check_tables", "cp_set_debug_validate", "cp_context_distance", "cp_probe_mfma",
            "cp_probe_mfma_sink_floats", "cp_probe_mfma_flops",
            "cp_index_distinct", "cp_index_build", "cp_index_free", "cp_index_num_contexts",
            "cp_index_num_nodes", "cp_index_aligned", "cp_index_path", "cp_index_leaf", "cp_index_node",
@@ -79,6 +82,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.cp_extend_attention.argtypes = [vp, vp, vp, vp, i32p, i32p, i32p, vp, vp, sp, vp, ctypes.c_size_t]
     lib.cp_write_kv.restype = ctypes.c_int
     lib.cp_write_kv.argtypes = [vp, vp, vp, i32p, i32p, i32p, vp, sp]
+    lib.cp_check_tables.restype = ctypes.c_int
+    lib.cp_check_tables.argtypes = [i32p, i32p, i32p, vp, sp, ctypes.POINTER(ctypes.c_int32)]
+    lib.cp_set_debug_validate.restype = None
+    lib.cp_set_debug_validate.argtypes = [ctypes.c_int]
     lib.cp_context_distance.restype = ctypes.c_int
     lib.cp_context_distance.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_float, vp, vp]
     lib.cp_probe_mfma.restype = ctypes.c_int
@@ -200,6 +207,20 @@ def cp_write_kv(k_new, v_new, kv_pages, block_table, prefix_lens, extend_lens, s
     if check and st != CP_OK:
         raise CpError(st, "cp_write_kv")
     return st
+
+
+def cp_check_tables(block_table, prefix_lens, extend_lens, stream, shape: Shape, check: bool = True):
+    """(status, [a, b, c]): see the header for the meaning of the three numbers."""
+    info = (ctypes.c_int32 * 3)(-1, -1, -1)
+    st = load_library().cp_check_tables(_ptr(block_table), _ptr(prefix_lens), _ptr(extend_lens),
+                                        _stream(stream), shape.ref(), info)
+    if check and st != CP_OK:
+        raise CpError(st, "cp_check_tables")
+    return st, [int(x) for x in info]
+
+
+def cp_set_debug_validate(on: bool) -> None:
+    load_library().cp_set_debug_validate(int(bool(on)))
 
 
 def cp_context_distance(contexts, lens, n: int, stride: int, alpha: float, dist, stream,

@@ -15,9 +15,13 @@
 // V^T fragments come from LDS through the transposing read ds_read_b64_tr_b16.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include <algorithm>
+#include <atomic>
+#include <mutex>
 #include <type_traits>
+#include <vector>
 
 #include "cp_extend.h"
 
@@ -994,6 +998,49 @@ __global__ __launch_bounds__(256) void write_kv_kernel(const uint16_t *__restric
     }
 }
 
+
+// ---- optional check of the device-side tables ------------------------------------------------
+// The attention and append kernels trust block_table and the device copies of the lengths.  This
+// kernel reads them without following any page id: thread (request r, slot i) looks at
+// block_table[r][i] for the slots the request uses, i < ceil((P_r + E_r) / 16), with P_r and E_r
+// taken from the device arrays, and records the first offence (smallest code of request and slot)
+// in a four-word report: {kind, request, slot, value}.
+constexpr int kCheckThreads = 256;
+enum : uint32_t { kCheckOk = 0u, kCheckBadLength = 1u, kCheckBadPage = 2u };
+__global__ __launch_bounds__(kCheckThreads) void check_tables_kernel(const int32_t *__restrict__ block_table,
+                                                                     const int32_t *__restrict__ prefix_lens,
+                                                                     const int32_t *__restrict__ extend_lens,
+                                                                     int batch, int max_pages, int num_pages,
+                                                                     unsigned long long *__restrict__ first_bad,
+                                                                     int32_t *__restrict__ bad_value)
+{
+    const int r = blockIdx.y;
+    if (r >= batch) return;
+    const int64_t P = prefix_lens[r], E = extend_lens[r];
+    const int64_t used = (P + E + kPS - 1) / kPS;
+    // key of an offence: kind in the top bits so that a bad length outranks a bad page, then the
+    // request, then the slot; the smallest key wins
+    auto report = [&](uint32_t kind, int slot, int32_t value) {
+        const unsigned long long key = ((unsigned long long)(kind == kCheckBadLength ? 0u : 1u) << 62) |
+                                       ((unsigned long long)(uint32_t)r << 31) | (unsigned long long)(uint32_t)slot;
+        const unsigned long long old = atomicMin(first_bad, key);
+        if (key < old) *bad_value = value; // informational only: the key decides the verdict
+    };
+    if (P < 0 || E < 0 || used > max_pages) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) report(kCheckBadLength, 0, (int32_t)(P < 0 ? P : E));
+        return;
+    }
+    for (int64_t i = (int64_t)blockIdx.x * kCheckThreads + threadIdx.x; i < used; i += (int64_t)gridDim.x * kCheckThreads) {
+        const int32_t page = block_table[(int64_t)r * max_pages + i];
+        if (page < 0 || page >= num_pages) report(kCheckBadPage, (int)i, page);
+    }
+}
+
+// Scratch of the check above and of the entry point that takes no workspace: file-scope device
+// arrays, so that no call allocates.  In host code the arrays' names are stand-ins, not device
+// addresses; the per-device address comes from hipGetSymbolAddress (device_scratch below).
+__device__ __align__(256) unsigned long long g_check_report[32];
+
 // ------------------------------------------------------------------ host side
 struct Plan {
     int64_t q_tiles;   // work units per KV head: row tiles x head groups, summed over requests
@@ -1003,31 +1050,35 @@ struct Plan {
     int32_t row_blocks; // ... in this many blocks of 32 rows
 };
 
+// Compute units of the device the first caller runs on (every device this library is built
+// for has the same count); read once, any number of host threads may race to be that caller.
 int num_cus()
 {
-    static int cached = 0;
-    if (cached == 0) {
-        int dev = 0, n = 0;
+    static std::atomic<int> cached{0};
+    int n = cached.load(std::memory_order_relaxed);
+    if (n == 0) {
+        int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
             n = 256;
-        cached = n;
+        cached.store(n, std::memory_order_relaxed);
     }
-    return cached;
+    return n;
 }
 
 // The attention kernel uses more LDS than the default per-workgroup limit; raise it once.
 bool allow_large_lds()
 {
-    static int state = 0; // 0 = not tried, 1 = ok, -1 = failed
-    if (state == 0) {
+    static std::once_flag once;
+    static bool ok = false;
+    std::call_once(once, [] {
         const hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void *>(&extend_attn_kernel<false>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         const hipError_t b = hipFuncSetAttribute(reinterpret_cast<const void *>(&extend_attn_kernel<true>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        state = (a == hipSuccess && b == hipSuccess) ? 1 : -1;
-    }
-    return state == 1;
+        ok = a == hipSuccess && b == hipSuccess;
+    });
+    return ok;
 }
 
 int validate(const cp_shape *s)
@@ -1113,6 +1164,102 @@ size_t workspace_for(const cp_shape *s, const Plan &pl)
     return ((o_bytes + 255) / 256) * 256 + ((ml_bytes + 255) / 256) * 256;
 }
 
+
+inline bool aligned_to(const void *p, uintptr_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
+
+// Device address of a file-scope __device__ array on the current device, looked up once per
+// device (every device holds its own copy at its own address).
+constexpr int kMaxDevices = 64;
+struct SymbolCache {
+    std::mutex lock;
+    void *addr[kMaxDevices] = {};
+};
+template <typename Lookup>
+void *device_address(SymbolCache &cache, Lookup lookup)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> guard(cache.lock);
+    if (!cache.addr[dev]) {
+        void *ptr = nullptr;
+        if (lookup(&ptr) != hipSuccess) return nullptr;
+        cache.addr[dev] = ptr;
+    }
+    return cache.addr[dev];
+}
+void *check_report_address()
+{
+    static SymbolCache cache;
+    return device_address(cache, [](void **ptr) { return hipGetSymbolAddress(ptr, HIP_SYMBOL(g_check_report)); });
+}
+
+std::atomic<int> g_debug_validate{
+#ifdef CP_DEBUG_VALIDATE
+    1
+#else
+    -1 // not decided yet: the environment variable CP_DEBUG_VALIDATE is read on first use
+#endif
+};
+bool debug_validate_on()
+{
+    int v = g_debug_validate.load(std::memory_order_relaxed);
+    if (v < 0) {
+        const char *e = getenv("CP_DEBUG_VALIDATE");
+        v = (e && e[0] && e[0] != '0') ? 1 : 0;
+        g_debug_validate.store(v, std::memory_order_relaxed);
+    }
+    return v == 1;
+}
+
+// The check itself: lengths are compared on the host after one copy, table entries on the
+// device.  Waits for `stream` (this is the one place where the library synchronises).
+int check_tables(const int32_t *block_table, const int32_t *prefix_lens, const int32_t *extend_lens,
+                 hipStream_t hs, const cp_shape *s, int32_t *info)
+{
+    if (info) info[0] = info[1] = info[2] = -1;
+    const int B = s->batch;
+    std::vector<int32_t> dev_p((size_t)B), dev_e((size_t)B);
+    if (hipMemcpyAsync(dev_p.data(), prefix_lens, (size_t)B * 4, hipMemcpyDeviceToHost, hs) != hipSuccess ||
+        hipMemcpyAsync(dev_e.data(), extend_lens, (size_t)B * 4, hipMemcpyDeviceToHost, hs) != hipSuccess ||
+        hipStreamSynchronize(hs) != hipSuccess)
+        return CP_ERR_LAUNCH;
+    for (int r = 0; r < B; ++r)
+        if (dev_p[r] != s->h_prefix_lens[r] || dev_e[r] != s->h_extend_lens[r]) {
+            if (info) {
+                info[0] = r;
+                info[1] = dev_p[r];
+                info[2] = dev_e[r];
+            }
+            return CP_ERR_LENGTHS;
+        }
+    auto *report = static_cast<unsigned long long *>(check_report_address());
+    if (!report) return CP_ERR_LAUNCH;
+    const unsigned long long clear[2] = {~0ull, 0ull};
+    if (hipMemcpyAsync(report, clear, sizeof(clear), hipMemcpyHostToDevice, hs) != hipSuccess) return CP_ERR_LAUNCH;
+    const int blocks_x = std::max(1, std::min(64, (s->max_pages_per_req + kCheckThreads - 1) / kCheckThreads));
+    for (int r0 = 0; r0 < B; r0 += 65535) { // grid.y limit
+        const int nb = std::min(65535, B - r0);
+        hipLaunchKernelGGL(check_tables_kernel, dim3((unsigned)blocks_x, (unsigned)nb), dim3(kCheckThreads), 0, hs,
+                           block_table + (int64_t)r0 * s->max_pages_per_req, prefix_lens + r0, extend_lens + r0, nb,
+                           s->max_pages_per_req, s->num_pages, report, reinterpret_cast<int32_t *>(report + 1));
+        if (hipGetLastError() != hipSuccess) return CP_ERR_LAUNCH;
+        unsigned long long got[2] = {0, 0};
+        if (hipMemcpyAsync(got, report, sizeof(got), hipMemcpyDeviceToHost, hs) != hipSuccess ||
+            hipStreamSynchronize(hs) != hipSuccess)
+            return CP_ERR_LAUNCH;
+        if (got[0] != ~0ull) {
+            const bool bad_page = (got[0] >> 62) != 0;
+            if (info) {
+                info[0] = r0 + (int32_t)((got[0] >> 31) & 0x7fffffffu);
+                info[1] = (int32_t)(got[0] & 0x7fffffffu);
+                info[2] = (int32_t)(uint32_t)got[1];
+            }
+            return bad_page ? CP_ERR_TABLE : CP_ERR_LENGTHS;
+        }
+    }
+    return CP_OK;
+}
+
 } // namespace
 
 extern "C" {
@@ -1125,6 +1272,9 @@ const char *cp_status_string(int status)
     case CP_ERR_SHAPE: return "unsupported or inconsistent shape";
     case CP_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
     case CP_ERR_LAUNCH: return "HIP launch error";
+    case CP_ERR_ALIGN: return "a device pointer is not aligned as required";
+    case CP_ERR_TABLE: return "block_table holds a page id outside [0, num_pages)";
+    case CP_ERR_LENGTHS: return "device prefix_lens / extend_lens differ from the host copies";
     default: return "unknown status";
     }
 }
@@ -1151,6 +1301,15 @@ int cp_extend_attention(const void *q, const void *k_new, const void *v_new, con
     if (!block_table || !prefix_lens || !extend_lens) return CP_ERR_NULL;
     if (shape->total_extend == 0) return CP_OK;
     if (!q || !k_new || !v_new || !kv_pages || !out) return CP_ERR_NULL;
+    if (!aligned_to(q, 16) || !aligned_to(k_new, 16) || !aligned_to(v_new, 16) || !aligned_to(kv_pages, 16) ||
+        !aligned_to(out, 16) || !aligned_to(block_table, 4) || !aligned_to(prefix_lens, 4) ||
+        !aligned_to(extend_lens, 4))
+        return CP_ERR_ALIGN;
+    if (debug_validate_on()) {
+        const int chk = check_tables(block_table, prefix_lens, extend_lens, static_cast<hipStream_t>(stream), shape,
+                                     nullptr);
+        if (chk != CP_OK) return chk;
+    }
     const Plan pl = make_plan(shape);
     const size_t need = workspace_for(shape, pl);
     if (need > 0) {
@@ -1228,6 +1387,14 @@ int cp_write_kv(const void *k_new, const void *v_new, void *kv_pages, const int3
     if (!block_table || !prefix_lens || !extend_lens) return CP_ERR_NULL;
     if (shape->total_extend == 0) return CP_OK;
     if (!k_new || !v_new || !kv_pages) return CP_ERR_NULL;
+    if (!aligned_to(k_new, 16) || !aligned_to(v_new, 16) || !aligned_to(kv_pages, 16) ||
+        !aligned_to(block_table, 4) || !aligned_to(prefix_lens, 4) || !aligned_to(extend_lens, 4))
+        return CP_ERR_ALIGN;
+    if (debug_validate_on()) {
+        const int chk = check_tables(block_table, prefix_lens, extend_lens, static_cast<hipStream_t>(stream), shape,
+                                     nullptr);
+        if (chk != CP_OK) return chk;
+    }
     const int T = shape->total_extend;
     const dim3 grid((unsigned)((T + kWriteRows - 1) / kWriteRows)), block(256);
     hipLaunchKernelGGL(write_kv_kernel, grid, block, 0, static_cast<hipStream_t>(stream),
@@ -1237,5 +1404,17 @@ int cp_write_kv(const void *k_new, const void *v_new, void *kv_pages, const int3
     if (hipGetLastError() != hipSuccess) return CP_ERR_LAUNCH;
     return CP_OK;
 }
+
+int cp_check_tables(const int32_t *block_table, const int32_t *prefix_lens, const int32_t *extend_lens,
+                    void *stream, const cp_shape *shape, int32_t *info)
+{
+    const int st = validate(shape);
+    if (st != CP_OK) return st;
+    if (!block_table || !prefix_lens || !extend_lens) return CP_ERR_NULL;
+    if (!aligned_to(block_table, 4) || !aligned_to(prefix_lens, 4) || !aligned_to(extend_lens, 4)) return CP_ERR_ALIGN;
+    return check_tables(block_table, prefix_lens, extend_lens, static_cast<hipStream_t>(stream), shape, info);
+}
+
+void cp_set_debug_validate(int on) { g_debug_validate.store(on ? 1 : 0, std::memory_order_relaxed); }
 
 } // extern "C"

@@ -38,8 +38,10 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_status_strings(lib):
     assert cp.cp_status_string(cp.CP_OK) == "ok"
-    for code in (cp.CP_ERR_NULL, cp.CP_ERR_SHAPE, cp.CP_ERR_WORKSPACE, cp.CP_ERR_LAUNCH, -99):
-        assert len(cp.cp_status_string(code)) > 3
+    texts = [cp.cp_status_string(code) for code in (cp.CP_ERR_NULL, cp.CP_ERR_SHAPE, cp.CP_ERR_WORKSPACE,
+                                                    cp.CP_ERR_LAUNCH, cp.CP_ERR_ALIGN, cp.CP_ERR_TABLE,
+                                                    cp.CP_ERR_LENGTHS, -99)]
+    assert all(len(t) > 3 for t in texts) and len(set(texts)) == len(texts)
 
 
 def _shape(P, E, Hq=32, Hkv=8, splits=0, D=128, PS=16, pages=None, width=None):
@@ -112,6 +114,31 @@ def test_null_pointers_and_missing_workspace_are_rejected_before_any_launch(lib)
     assert cp.cp_write_kv(None, 1, 1, 1, 1, 1, None, ok, check=False) == cp.CP_ERR_NULL
     with pytest.raises(cp.CpError):
         cp.cp_write_kv(None, 1, 1, 1, 1, 1, None, ok)
+
+
+def test_misaligned_device_pointers_are_rejected_before_any_launch(lib):
+    """q, k_new, v_new, kv_pages and out are moved in 16-byte pieces, the int32 arrays in 4-byte
+    ones: every pointer is checked on the host, one at a time here."""
+    ok = _shape([32], [32], Hq=4, Hkv=2, splits=1)
+    base = [4096] * 8                      # q, k_new, v_new, kv_pages, table, prefix, extend, out
+    for slot in (0, 1, 2, 3, 7):
+        for off in (2, 8):
+            args = list(base)
+            args[slot] += off
+            assert cp.cp_extend_attention(*args, None, ok, None, 0, check=False) == cp.CP_ERR_ALIGN
+    for slot in (4, 5, 6):
+        args = list(base)
+        args[slot] += 2
+        assert cp.cp_extend_attention(*args, None, ok, None, 0, check=False) == cp.CP_ERR_ALIGN
+    wbase = [4096] * 6                     # k_new, v_new, kv_pages, table, prefix, extend
+    for slot, off in ((0, 8), (1, 4), (2, 2), (3, 1), (4, 2), (5, 3)):
+        args = list(wbase)
+        args[slot] += off
+        assert cp.cp_write_kv(*args, None, ok, check=False) == cp.CP_ERR_ALIGN
+    st, info = cp.cp_check_tables(4098, 4096, 4096, None, ok, check=False)
+    assert st == cp.CP_ERR_ALIGN and info == [-1, -1, -1]
+    st, _ = cp.cp_check_tables(None, 4096, 4096, None, ok, check=False)
+    assert st == cp.CP_ERR_NULL
 
 
 def test_empty_batch_is_a_no_op(lib):
