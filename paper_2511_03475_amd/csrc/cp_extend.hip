@@ -1004,15 +1004,14 @@ __global__ __launch_bounds__(256) void write_kv_kernel(const uint16_t *__restric
 // kernel reads them without following any page id: thread (request r, slot i) looks at
 // block_table[r][i] for the slots the request uses, i < ceil((P_r + E_r) / 16), with P_r and E_r
 // taken from the device arrays, and records the first offence (smallest code of request and slot)
-// in a four-word report: {kind, request, slot, value}.
+// in one 64-bit word.
 constexpr int kCheckThreads = 256;
 enum : uint32_t { kCheckOk = 0u, kCheckBadLength = 1u, kCheckBadPage = 2u };
 __global__ __launch_bounds__(kCheckThreads) void check_tables_kernel(const int32_t *__restrict__ block_table,
                                                                      const int32_t *__restrict__ prefix_lens,
                                                                      const int32_t *__restrict__ extend_lens,
                                                                      int batch, int max_pages, int num_pages,
-                                                                     unsigned long long *__restrict__ first_bad,
-                                                                     int32_t *__restrict__ bad_value)
+                                                                     unsigned long long *__restrict__ first_bad)
 {
     const int r = blockIdx.y;
     if (r >= batch) return;
@@ -1020,19 +1019,18 @@ __global__ __launch_bounds__(kCheckThreads) void check_tables_kernel(const int32
     const int64_t used = (P + E + kPS - 1) / kPS;
     // key of an offence: kind in the top bits so that a bad length outranks a bad page, then the
     // request, then the slot; the smallest key wins
-    auto report = [&](uint32_t kind, int slot, int32_t value) {
+    auto report = [&](uint32_t kind, int slot) {
         const unsigned long long key = ((unsigned long long)(kind == kCheckBadLength ? 0u : 1u) << 62) |
                                        ((unsigned long long)(uint32_t)r << 31) | (unsigned long long)(uint32_t)slot;
-        const unsigned long long old = atomicMin(first_bad, key);
-        if (key < old) *bad_value = value; // informational only: the key decides the verdict
+        atomicMin(first_bad, key);
     };
     if (P < 0 || E < 0 || used > max_pages) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) report(kCheckBadLength, 0, (int32_t)(P < 0 ? P : E));
+        if (blockIdx.x == 0 && threadIdx.x == 0) report(kCheckBadLength, 0);
         return;
     }
     for (int64_t i = (int64_t)blockIdx.x * kCheckThreads + threadIdx.x; i < used; i += (int64_t)gridDim.x * kCheckThreads) {
         const int32_t page = block_table[(int64_t)r * max_pages + i];
-        if (page < 0 || page >= num_pages) report(kCheckBadPage, (int)i, page);
+        if (page < 0 || page >= num_pages) report(kCheckBadPage, (int)i);
     }
 }
 
@@ -1234,25 +1232,31 @@ int check_tables(const int32_t *block_table, const int32_t *prefix_lens, const i
         }
     auto *report = static_cast<unsigned long long *>(check_report_address());
     if (!report) return CP_ERR_LAUNCH;
-    const unsigned long long clear[2] = {~0ull, 0ull};
-    if (hipMemcpyAsync(report, clear, sizeof(clear), hipMemcpyHostToDevice, hs) != hipSuccess) return CP_ERR_LAUNCH;
+    const unsigned long long clear = ~0ull;
+    if (hipMemcpyAsync(report, &clear, sizeof(clear), hipMemcpyHostToDevice, hs) != hipSuccess) return CP_ERR_LAUNCH;
     const int blocks_x = std::max(1, std::min(64, (s->max_pages_per_req + kCheckThreads - 1) / kCheckThreads));
     for (int r0 = 0; r0 < B; r0 += 65535) { // grid.y limit
         const int nb = std::min(65535, B - r0);
         hipLaunchKernelGGL(check_tables_kernel, dim3((unsigned)blocks_x, (unsigned)nb), dim3(kCheckThreads), 0, hs,
                            block_table + (int64_t)r0 * s->max_pages_per_req, prefix_lens + r0, extend_lens + r0, nb,
-                           s->max_pages_per_req, s->num_pages, report, reinterpret_cast<int32_t *>(report + 1));
+                           s->max_pages_per_req, s->num_pages, report);
         if (hipGetLastError() != hipSuccess) return CP_ERR_LAUNCH;
-        unsigned long long got[2] = {0, 0};
-        if (hipMemcpyAsync(got, report, sizeof(got), hipMemcpyDeviceToHost, hs) != hipSuccess ||
+        unsigned long long got = 0;
+        if (hipMemcpyAsync(&got, report, sizeof(got), hipMemcpyDeviceToHost, hs) != hipSuccess ||
             hipStreamSynchronize(hs) != hipSuccess)
             return CP_ERR_LAUNCH;
-        if (got[0] != ~0ull) {
-            const bool bad_page = (got[0] >> 62) != 0;
+        if (got != ~0ull) {
+            const bool bad_page = (got >> 62) != 0;
+            const int r = r0 + (int)((got >> 31) & 0x7fffffffu), slot = (int)(got & 0x7fffffffu);
+            int32_t entry = -1;
+            if (bad_page && (hipMemcpyAsync(&entry, block_table + (int64_t)r * s->max_pages_per_req + slot, 4,
+                                            hipMemcpyDeviceToHost, hs) != hipSuccess ||
+                             hipStreamSynchronize(hs) != hipSuccess))
+                return CP_ERR_LAUNCH;
             if (info) {
-                info[0] = r0 + (int32_t)((got[0] >> 31) & 0x7fffffffu);
-                info[1] = (int32_t)(got[0] & 0x7fffffffu);
-                info[2] = (int32_t)(uint32_t)got[1];
+                info[0] = r;
+                info[1] = bad_page ? slot : dev_p[r];
+                info[2] = bad_page ? entry : dev_e[r];
             }
             return bad_page ? CP_ERR_TABLE : CP_ERR_LENGTHS;
         }
