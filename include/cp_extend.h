@@ -110,6 +110,26 @@ int cp_extend_attention(const void *q, const void *k_new, const void *v_new,
                         size_t workspace_bytes);
 
 /*
+ * cp_extend_attention for callers that cannot allocate device memory or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, result and checks as cp_extend_attention without the last two; the split-K /
+ * decode partial results go to an array of cp_noalloc_scratch_bytes() bytes (64 MiB) that lives
+ * inside the library, once per device, from the moment the library is loaded until the process
+ * ends.  A shape whose cp_workspace_bytes exceeds that size is refused with CP_ERR_WORKSPACE
+ * and nothing is launched.  The call allocates nothing and frees nothing (the array's device
+ * address is looked up on the first call on each device).  All calls on one device share the
+ * array: two such calls that overlap in time (different streams, different host threads) race
+ * on it and must be serialised by the caller; calls on one stream are ordered and safe.
+ */
+int cp_extend_attention_noalloc(const void *q, const void *k_new, const void *v_new,
+                                const void *kv_pages, const int32_t *block_table,
+                                const int32_t *prefix_lens, const int32_t *extend_lens,
+                                void *out, void *stream, const cp_shape *shape);
+
+/* Size in bytes of the array behind cp_extend_attention_noalloc: its largest workspace. */
+size_t cp_noalloc_scratch_bytes(void);
+
+/*
  * Cache append (paper, Section 1: the prefix cache stores the K/V of prior prompts).  For
  * request r, row j < E_r and KV head g, the bit patterns of k_new[cu[r]+j, g, :] and
  * v_new[cu[r]+j, g, :] are copied to page block_table[r][(P_r+j) / PS], slot (P_r+j) % PS.

@@ -25,6 +25,7 @@ CP_ERR_TABLE = -6
 CP_ERR_LENGTHS = -7
 
 EXPORTS = ("cp_workspace_bytes", "cp_num_splits", "cp_extend_attention", "cp_write_kv",
+           "cp_extend_attention_noalloc", "cp_noalloc_scratch_bytes",
            "cp_status_string", "cp_check_tables", "cp_set_debug_validate", "cp_context_distance", "cp_probe_mfma",
            "cp_probe_mfma_sink_floats", "cp_probe_mfma_flops",
            "cp_index_distinct", "cp_index_build", "cp_index_free", "cp_index_num_contexts",
@@ -80,6 +81,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.cp_num_splits.argtypes = [sp]
     lib.cp_extend_attention.restype = ctypes.c_int
     lib.cp_extend_attention.argtypes = [vp, vp, vp, vp, i32p, i32p, i32p, vp, vp, sp, vp, ctypes.c_size_t]
+    lib.cp_extend_attention_noalloc.restype = ctypes.c_int
+    lib.cp_extend_attention_noalloc.argtypes = [vp, vp, vp, vp, i32p, i32p, i32p, vp, vp, sp]
+    lib.cp_noalloc_scratch_bytes.restype = ctypes.c_size_t
+    lib.cp_noalloc_scratch_bytes.argtypes = []
     lib.cp_write_kv.restype = ctypes.c_int
     lib.cp_write_kv.argtypes = [vp, vp, vp, i32p, i32p, i32p, vp, sp]
     lib.cp_check_tables.restype = ctypes.c_int
@@ -197,6 +202,20 @@ def cp_extend_attention(q, k_new, v_new, kv_pages, block_table, prefix_lens, ext
     if check and st != CP_OK:
         raise CpError(st, "cp_extend_attention")
     return st
+
+
+def cp_extend_attention_noalloc(q, k_new, v_new, kv_pages, block_table, prefix_lens, extend_lens, out,
+                                stream, shape: Shape, check: bool = True) -> int:
+    st = load_library().cp_extend_attention_noalloc(
+        _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_pages), _ptr(block_table), _ptr(prefix_lens),
+        _ptr(extend_lens), _ptr(out), _stream(stream), shape.ref())
+    if check and st != CP_OK:
+        raise CpError(st, "cp_extend_attention_noalloc")
+    return st
+
+
+def cp_noalloc_scratch_bytes() -> int:
+    return int(load_library().cp_noalloc_scratch_bytes())
 
 
 def cp_write_kv(k_new, v_new, kv_pages, block_table, prefix_lens, extend_lens, stream,

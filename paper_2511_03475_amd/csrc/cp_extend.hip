@@ -1266,6 +1266,21 @@ int check_tables(const int32_t *block_table, const int32_t *prefix_lens, const i
 
 } // namespace
 
+// Split-K / decode partial results of cp_extend_attention_noalloc: one array per device, held
+// until the process ends.  Nothing in it has to start at zero (every partial that the merge
+// reads is written by the launch before it), so it is never cleared; calls that overlap on one
+// device share it and race.
+#define CP_NOALLOC_SCRATCH_BYTES (64u << 20)
+static __device__ __align__(256) unsigned char scratch[CP_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+void *scratch_address()
+{
+    static SymbolCache cache;
+    return device_address(cache, [](void **ptr) { return hipGetSymbolAddress(ptr, HIP_SYMBOL(scratch)); });
+}
+} // namespace
+
 extern "C" {
 
 const char *cp_status_string(int status)
@@ -1295,10 +1310,14 @@ size_t cp_workspace_bytes(const cp_shape *shape)
     return workspace_for(shape, make_plan(shape));
 }
 
-int cp_extend_attention(const void *q, const void *k_new, const void *v_new, const void *kv_pages,
-                        const int32_t *block_table, const int32_t *prefix_lens,
-                        const int32_t *extend_lens, void *out, void *stream, const cp_shape *shape,
-                        void *workspace, size_t workspace_bytes)
+} // extern "C"
+
+namespace {
+// Everything behind cp_extend_attention: argument checks, plan, launches.  `workspace` is
+// whatever scratch the entry point brings: the caller's buffer or the library's own array.
+int run_attention(const void *q, const void *k_new, const void *v_new, const void *kv_pages,
+                  const int32_t *block_table, const int32_t *prefix_lens, const int32_t *extend_lens, void *out,
+                  void *stream, const cp_shape *shape, void *workspace, size_t workspace_bytes)
 {
     const int st = validate(shape);
     if (st != CP_OK) return st;
@@ -1380,6 +1399,34 @@ int cp_extend_attention(const void *q, const void *k_new, const void *v_new, con
     }
     if (hipGetLastError() != hipSuccess) return CP_ERR_LAUNCH;
     return CP_OK;
+}
+} // namespace
+
+extern "C" {
+
+int cp_extend_attention(const void *q, const void *k_new, const void *v_new, const void *kv_pages,
+                        const int32_t *block_table, const int32_t *prefix_lens,
+                        const int32_t *extend_lens, void *out, void *stream, const cp_shape *shape,
+                        void *workspace, size_t workspace_bytes)
+{
+    return run_attention(q, k_new, v_new, kv_pages, block_table, prefix_lens, extend_lens, out, stream, shape,
+                         workspace, workspace_bytes);
+}
+
+size_t cp_noalloc_scratch_bytes(void) { return CP_NOALLOC_SCRATCH_BYTES; }
+
+int cp_extend_attention_noalloc(const void *q, const void *k_new, const void *v_new, const void *kv_pages,
+                                const int32_t *block_table, const int32_t *prefix_lens,
+                                const int32_t *extend_lens, void *out, void *stream, const cp_shape *shape)
+{
+    const int st = validate(shape);
+    if (st != CP_OK) return st;
+    // sizes beyond the library's own array are refused here, before anything is looked up or launched
+    if (workspace_for(shape, make_plan(shape)) > CP_NOALLOC_SCRATCH_BYTES) return CP_ERR_WORKSPACE;
+    void *ptr = scratch_address(); // the array's address on the current device, never the array's name
+    if (!ptr) return CP_ERR_LAUNCH;
+    return run_attention(q, k_new, v_new, kv_pages, block_table, prefix_lens, extend_lens, out, stream, shape, ptr,
+                         CP_NOALLOC_SCRATCH_BYTES);
 }
 
 int cp_write_kv(const void *k_new, const void *v_new, void *kv_pages, const int32_t *block_table,
