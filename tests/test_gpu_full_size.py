@@ -66,6 +66,54 @@ def test_config5_128k_zero_reuse_and_reuse_sampled(H):
     _sampled(H, wb, rows, "config5b 87.5% reuse")
 
 
+def test_config5_reuse_run_equals_the_last_rows_of_the_zero_reuse_run(H):
+    """Both 128k runs see the same token streams (the reuse run's pages hold the first 114688
+    K/V rows of the zero-reuse run, its q / k_new / v_new are the last 16384 rows), so the two
+    outputs must agree row for row: each is one bf16 rounding of nearly the same fp32 value, hence
+    at most two bf16 steps apart."""
+    wa = W.config5_128k(False)
+    full = bf16_bits_to_f32(H.gpu_attention(wa)[114688:]).astype(np.float64)
+    del wa
+    wb = W.config5_128k(True)
+    part = bf16_bits_to_f32(H.gpu_attention(wb)).astype(np.float64)
+    assert part.shape == full.shape == (16384, 32, 128)
+    step = np.maximum(np.abs(full), np.abs(part)) * 2.0 ** -7      # one bf16 step is at most 2^-7 of the value
+    assert (np.abs(full - part) <= 2.0 * step + 1e-30).all()
+    assert (full == part).mean() > 0.9
+
+
+def _bench_workload(name):
+    import bench
+    return bench._workload(name)
+
+
+@pytest.mark.parametrize("name,q_block", [("short_extend_probe", 64), ("rag_zipf_as_retrieved", 1024),
+                                          ("rag_zipf_context_index", 1024)])
+def test_other_timed_extend_shapes_sampled(H, name, q_block):
+    """Shapes that bench.py times beside the five configs, at the size timed: the short-extend
+    probe (32 requests x 128 new tokens over 10240 cached, two q heads packed per workgroup) and
+    the Zipf batch in the other two block orders (as retrieved; aligned and scheduled by the
+    context index)."""
+    w = _bench_workload(name)
+    rows = W.sample_rows(w, 21, q_block=q_block, edge=4, seams=2)
+    _sampled(H, w, rows, name)
+
+
+def test_other_timed_decode_shapes(H):
+    """decode_b32_p10k_e16: 16 new tokens per request (two blocks of 32 rows per KV head, four key
+    chunks), every row checked.  decode_b1_p128k: one token over 131072 cached tokens, 256 key
+    chunks merged."""
+    w = _bench_workload("decode_b32_p10k_e16")
+    assert w.total_extend == 512
+    _check(H.gpu_attention(w), oracle.attention_of(w), "decode_b32_p10k_e16, all 512 rows")
+    del w
+    w = _bench_workload("decode_b1_p128k")
+    import paper_2511_03475_amd as cp
+    from gpu_harness import DeviceCase
+    assert cp.cp_num_splits(DeviceCase(w).shape) == 256
+    _check(H.gpu_attention(w), oracle.attention_of(w), "decode_b1_p128k")
+
+
 def test_chunked_prefill_and_decode_workloads_sampled(H):
     """The other shapes bench.py times: one 2048-token chunk over 16k cached tokens, and the
     decode batch (32 requests x 10240 cached tokens, one new token each; decode-shaped kernel)."""

@@ -99,3 +99,26 @@ def test_config3_is_the_frequency_sorted_special_case():
     picks = W.rag_zipf_picks(batch=6, topk=4, pool_ids=12)
     assert len(picks) == 6 and all(len(set(p)) == 4 for p in picks)
     assert W.rag_zipf_picks(batch=6, topk=4, pool_ids=12) == picks, "seeded"
+
+
+def test_config5_runs_share_their_token_streams():
+    """The reuse run is the zero-reuse run with its first rows moved into the cache: same q / k / v
+    bits for the last rows, same block table, pages filled with the first rows' K/V."""
+    total, cached = 4096 + 160, 4096
+    a, b = W.config5_128k(False, total=total, cached=cached), W.config5_128k(True, total=total, cached=cached)
+    _check_tables(a)
+    _check_tables(b)
+    assert a.prefix_lens.tolist() == [0] and b.prefix_lens.tolist() == [cached]
+    np.testing.assert_array_equal(b.q, a.q[cached:])
+    np.testing.assert_array_equal(b.k_new, a.k_new[cached:])
+    np.testing.assert_array_equal(b.v_new, a.v_new[cached:])
+    np.testing.assert_array_equal(a.block_table, b.block_table)
+    for tok in (0, 15, 16, 2047, cached - 1):
+        page, slot = b.block_table[0, tok // 16], tok % 16
+        np.testing.assert_array_equal(b.kv_pages[page, 0, :, slot, :], a.k_new[tok])
+        np.testing.assert_array_equal(b.kv_pages[page, 1, :, slot, :], a.v_new[tok])
+    # rows drawn on their own equal the same rows of the whole array
+    import workloads.generate as G
+    whole = G.normal_bf16(np.random.default_rng(5), (3000, 7, 128), chunk_elems=1 << 16)
+    part = G.normal_bf16_rows(np.random.default_rng(5), (3000, 7, 128), 1234, 2999, chunk_elems=1 << 16)
+    np.testing.assert_array_equal(part, whole[1234:2999])

@@ -73,6 +73,34 @@ def normal_bf16(rng: np.random.Generator, shape, chunk_elems: int = 1 << 23,
     return out.reshape(shape)
 
 
+def normal_bf16_rows(rng: np.random.Generator, shape, row_lo: int, row_hi: int,
+                     chunk_elems: int = 1 << 23, threads: int = 8) -> np.ndarray:
+    """Rows [row_lo, row_hi) of normal_bf16(rng, shape), without drawing the other rows: only the
+    chunks that overlap the slice are filled (chunk c always comes from child generator c)."""
+    n = int(np.prod(shape, dtype=np.int64))
+    row = n // int(shape[0])
+    lo, hi = row_lo * row, row_hi * row
+    nchunks = (n + chunk_elems - 1) // chunk_elems
+    children = rng.spawn(nchunks)
+    out = np.empty(hi - lo, dtype=np.uint16)
+
+    def fill(c):
+        c_lo, c_hi = c * chunk_elems, min((c + 1) * chunk_elems, n)
+        vals = f32_to_bf16_bits(children[c].standard_normal(c_hi - c_lo, dtype=np.float32))
+        a, b = max(c_lo, lo), min(c_hi, hi)
+        out[a - lo:b - lo] = vals[a - c_lo:b - c_lo]
+
+    todo = [c for c in range(nchunks) if c * chunk_elems < hi and min((c + 1) * chunk_elems, n) > lo]
+    if len(todo) <= 1 or threads <= 1:
+        for c in todo:
+            fill(c)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            list(ex.map(fill, todo))
+    return out.reshape((row_hi - row_lo,) + tuple(shape[1:]))
+
+
 @dataclasses.dataclass
 class Workload:
     name: str
@@ -275,10 +303,36 @@ def config4_long_context(seed: int = BASE_SEED + 4, batch: int = 4, prefix: int 
 
 def config5_128k(reuse: bool, seed: int = BASE_SEED + 5, total: int = 131072,
                  cached: int = 114688, Hq: int = 32, Hkv: int = 8) -> Workload:
-    """One 128k-token request: zero reuse (full causal prefill) or 87.5 % reuse."""
-    if reuse:
-        return make_uniform("ctx128k_reuse", seed, 1, Hq, Hkv, cached, total - cached)
-    return make_uniform("ctx128k_zero_reuse", seed, 1, Hq, Hkv, 0, total, fill_pool=False)
+    """One 128k-token request: zero reuse (full causal prefill) or 87.5 % reuse.
+
+    Both runs see the same token streams: the reuse run's q / k_new / v_new are the last
+    total - cached rows of the zero-reuse run's, its cached pages hold the K/V of the first
+    `cached` rows, and the block tables are equal.  The reuse run's output therefore equals the
+    last rows of the zero-reuse run's output up to rounding.
+    """
+    if not reuse:
+        return make_uniform("ctx128k_zero_reuse", seed, 1, Hq, Hkv, 0, total, fill_pool=False)
+    rq, rk, rv, _, rpages, _ = _streams(seed)
+    D, PS = HEAD_DIM, PAGE_SIZE
+    assert cached % PS == 0 and 0 < cached < total
+    num_pages = (total + PS - 1) // PS
+    table = rpages.permutation(num_pages).astype(np.int32)[None, :]      # as make_uniform places them
+    q = normal_bf16_rows(rq, (total, Hq, D), cached, total)
+    k_all_lo = normal_bf16_rows(rk, (total, Hkv, D), 0, cached)
+    v_all_lo = normal_bf16_rows(rv, (total, Hkv, D), 0, cached)
+    _, rk, rv, _, _, _ = _streams(seed)       # a generator hands out its children only once
+    k_new = normal_bf16_rows(rk, (total, Hkv, D), cached, total)
+    v_new = normal_bf16_rows(rv, (total, Hkv, D), cached, total)
+    kv_pages = np.zeros((num_pages, 2, Hkv, PS, D), dtype=np.uint16)
+    pp = cached // PS
+    kv_pages[table[0, :pp], 0] = k_all_lo.reshape(pp, PS, Hkv, D).transpose(0, 2, 1, 3)
+    kv_pages[table[0, :pp], 1] = v_all_lo.reshape(pp, PS, Hkv, D).transpose(0, 2, 1, 3)
+    return Workload(
+        name="ctx128k_reuse", batch=1, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, page_size=PS,
+        num_pages=num_pages, max_pages_per_req=num_pages, softmax_scale=1.0 / math.sqrt(D),
+        prefix_lens=np.array([cached], np.int32), extend_lens=np.array([total - cached], np.int32),
+        block_table=np.ascontiguousarray(table), q=q, k_new=k_new, v_new=v_new, kv_pages=kv_pages,
+        notes={"shares_streams_with": "ctx128k_zero_reuse"})
 
 
 def probe_short_extend(seed: int = BASE_SEED + 6, batch: int = 32, prefix: int = 10240,
