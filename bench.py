@@ -6,6 +6,7 @@ cp_extend_attention (suffix rows attend to cached prefix + own keys) over one ba
 synthetic input that is already resident in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-extra] [--no-cpu]
+                  [--operands normal|constant] [--splits N]
 """
 from __future__ import annotations
 
@@ -24,11 +25,13 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM bytes per launch of extend_attn_kernel from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0 +
-# WRITE_SIZE x 1.0, scale factors from a 1 GiB device copy in the same run), valid only for the
-# kernel source they were taken with: reported as null as soon as that source changes.
+# HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, scale
+# factors from a 1 GiB device copy in the same run), taken from the summaries under profiles/ and
+# valid only for the kernel source they were taken with: reported as null as soon as that source
+# changes.  They are not measured by this script.
 TRAFFIC = {
     "source_sha256_16": "345b83203334e8fd",
+    "from": "profiles/extend_attn_kernel_long_context_32k.md, profiles/decode_attn_kernel_decode_b32_p10k.md",
     "long_context_32k": (2130348 * 2.0 + 524288) * 1024.0,      # extend_attn_kernel
     "decode_b32_p10k": (656159 * 2.0 + 4161) * 1024.0,          # decode_attn_kernel
 }
@@ -49,14 +52,15 @@ def measured_traffic(workload: str):
 def roofline_of(workload: str, head: dict) -> dict:
     """Roofline entry of the dominant kernel: the matrix pipe when the call has more flops per
     algorithmic byte than the machine balance (2.5 PFLOP/s / 8 TB/s), HBM otherwise."""
-    if head["flops"] / head["alg_bytes"] >= PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
-        return {"bound": "mfma", "kernel": "extend_attn_kernel", "achieved": head["tflops_attn"],
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": head["frac_mfma_peak"],
-                "traffic": measured_traffic(workload), "avg_kernel_ms": head["attn_ms_avg"]}
-    return {"bound": "hbm", "kernel": "decode_attn_kernel + merge_splits_kernel" if head["splits"] % 4 == 0
-            else "extend_attn_kernel (+ merge_splits_kernel)", "achieved": head["gbs_attn"],
-            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": head["frac_hbm_peak"],
-            "traffic": measured_traffic(workload), "avg_kernel_ms": head["attn_ms_avg"]}
+    traffic = measured_traffic(workload)
+    common = {"kernel": head["kernels"], "traffic": traffic,
+              "traffic_source": TRAFFIC["from"] if traffic is not None else None,
+              "avg_kernel_ms": head["attn_ms_avg"], "median_kernel_ms": head["attn_ms_median"]}
+    if head["flops"] / head["alg_bytes_attn"] >= PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+        return {"bound": "mfma", "achieved": head["tflops_attn"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": head["frac_mfma_peak"], **common}
+    return {"bound": "hbm", "achieved": head["gbs_attn"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": head["frac_hbm_peak"], **common}
 
 
 def _workload(name: str):
@@ -64,6 +68,8 @@ def _workload(name: str):
     table = {
         "tiny_extend": W.config1_tiny,
         "rag_fixed": W.config2_rag_fixed,
+        # all 8 requests alias one cached 384-page prefix (the paper's multi-session case, Section 3.2)
+        "rag_fixed_shared_prefix": lambda: W.config2_rag_fixed(shared_prefix=True),
         "rag_zipf": W.config3_rag_zipf,
         "long_context_32k": W.config4_long_context,
         "ctx128k_zero_reuse": lambda: W.config5_128k(False),
@@ -108,22 +114,28 @@ def rag_zipf_context_index():
     return W.rag_batch_from_blocks("rag_zipf_context_index", W.BASE_SEED + 3, aligned, order=order)
 
 
-def algorithmic_bytes(w) -> float:
-    """Bytes that must move once: q in, out, new K/V read twice (attention, cache write) and
-    written once, every distinct prefix page once per request."""
+def algorithmic_bytes(w, with_cache_write: bool) -> float:
+    """Bytes that must move once.  The attention call: q in, out, the new K/V read once, every
+    prefix token's K/V once per request.  The whole step adds the cache append: the new K/V read
+    and written once more."""
     T, Hq, Hkv, D = w.total_extend, w.num_q_heads, w.num_kv_heads, w.head_dim
     q_out = 2.0 * T * Hq * D * 2
-    new_kv = 3.0 * T * Hkv * D * 2 * 2
+    new_kv = T * Hkv * D * 2 * 2.0
     prefix = float(w.prefix_lens.astype(np.int64).sum()) * Hkv * D * 2 * 2
-    return q_out + new_kv + prefix
+    return q_out + new_kv + prefix + (2.0 * new_kv if with_cache_write else 0.0)
 
 
 class Runner:
-    def __init__(self, w):
+    def __init__(self, w, num_splits: int = 0):
         import torch
         import paper_2511_03475_amd as cp
         self.torch, self.cp, self.w = torch, cp, w
         dev = "cuda:0"
+        if OPERANDS == "constant":
+            # every q, K and V element becomes bf16 1.0: same instructions and addresses, the
+            # fewest toggling bits; shows what the power limit costs on N(0,1) operands
+            for a in (w.q, w.k_new, w.v_new, w.kv_pages):
+                a[...] = 0x3F80
 
         def up(a):
             a = np.ascontiguousarray(a)
@@ -136,10 +148,11 @@ class Runner:
         self.out = torch.empty_like(self.q)
         self.shape = cp.Shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.page_size,
                               w.num_pages, w.max_pages_per_req, w.prefix_lens, w.extend_lens,
-                              w.softmax_scale)
+                              w.softmax_scale, num_splits=num_splits)
         self.ws_bytes = cp.cp_workspace_bytes(self.shape)
         self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=dev)
         self.splits = cp.cp_num_splits(self.shape)
+        self.kernels = cp.PLAN_KERNELS.get(cp.cp_plan_kind(self.shape), "?")
 
     def step(self, stream, ev=None):
         cp = self.cp
@@ -175,36 +188,84 @@ class Runner:
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         attn_ms = [a.elapsed_time(b) for a, b in events]
-        return (t1 - t0) * 1e3 / steps, float(np.mean(attn_ms)), float(np.min(attn_ms))
+        return (t1 - t0) * 1e3 / steps, attn_ms
 
 
 SETTLE_MS = 100.0   # untimed run-in before the warm-up steps, see Runner.run
+OPERANDS = "normal"  # "constant": see Runner.__init__
 
 
-def measure(name: str, steps: int, warmup: int):
+def measure(name: str, steps: int, warmup: int, num_splits: int = 0):
     t = time.perf_counter()
     w = _workload(name)
     gen_s = time.perf_counter() - t
-    r = Runner(w)
-    ms_step, attn_ms, attn_min = r.run(steps, warmup, SETTLE_MS)
+    r = Runner(w, num_splits)
+    ms_step, attn = r.run(steps, warmup, SETTLE_MS)
+    attn_ms, attn_med, attn_min = float(np.mean(attn)), float(np.median(attn)), float(np.min(attn))
     flops = w.flops()
+    b_attn, b_step = algorithmic_bytes(w, False), algorithmic_bytes(w, True)
     res = {
         "workload": name, "batch": w.batch, "q_heads": w.num_q_heads, "kv_heads": w.num_kv_heads,
         "prefix_tokens": int(w.prefix_lens.astype(np.int64).sum()), "extend_tokens": w.total_extend,
-        "flops": flops, "splits": r.splits, "steps": steps,
-        "ms_per_step": ms_step, "attn_ms_avg": attn_ms, "attn_ms_min": attn_min,
+        "flops": flops, "splits": r.splits, "forced_splits": num_splits, "kernels": r.kernels, "steps": steps,
+        "ms_per_step": ms_step, "attn_ms_avg": attn_ms, "attn_ms_median": attn_med, "attn_ms_min": attn_min,
         "tflops_step": flops / (ms_step * 1e-3) / 1e12,
         "tflops_attn": flops / (attn_ms * 1e-3) / 1e12,
         "frac_mfma_peak": flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-        "alg_bytes": algorithmic_bytes(w),
-        "gbs_step": algorithmic_bytes(w) / (ms_step * 1e-3) / 1e9,
-        "gbs_attn": algorithmic_bytes(w) / (attn_ms * 1e-3) / 1e9,
-        "frac_hbm_peak": algorithmic_bytes(w) / (attn_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "alg_bytes_attn": b_attn, "alg_bytes_step": b_step,
+        "gbs_step": b_step / (ms_step * 1e-3) / 1e9,
+        "gbs_attn": b_attn / (attn_ms * 1e-3) / 1e9,
+        "frac_hbm_peak": b_attn / (attn_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "gen_s": gen_s,
     }
+    if COPY_CEILING_GBS:
+        res["frac_hbm_copy_ceiling"] = res["gbs_attn"] / COPY_CEILING_GBS
     if w.notes:
         res["notes"] = {k: v for k, v in w.notes.items()}
     return w, r, res
+
+
+COPY_CEILING_GBS = None   # what a plain device-to-device copy moves on this device, set by main()
+
+
+def measure_copy_ceiling(nbytes: int = 1 << 30, steps: int = 20) -> float:
+    """GB/s (read + write) of a plain 1 GiB device-to-device copy kernel: the HBM rate this device
+    gives a kernel that does nothing else, to put beside the published 8 TB/s."""
+    import torch
+    import paper_2511_03475_amd as cp
+    a = torch.empty(nbytes // 4, dtype=torch.int32, device="cuda:0").fill_(1)
+    b = torch.empty_like(a)
+    stream = torch.cuda.current_stream()
+    for _ in range(150):   # ~50 ms of the same load first, as for the workloads
+        cp.cp_probe_copy(b, a, nbytes, stream)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    ev[0].record(stream)
+    for i in range(steps):
+        cp.cp_probe_copy(b, a, nbytes, stream)
+        ev[i + 1].record(stream)
+    torch.cuda.synchronize()
+    ms = float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]))
+    del a, b
+    torch.cuda.empty_cache()
+    return 2.0 * nbytes / (ms * 1e-3) / 1e9
+
+
+def device_state() -> dict:
+    """Clocks and power as rocm-smi prints them right after the timed runs (a child process;
+    best effort: an empty dict when the tool is missing or refuses)."""
+    import shutil
+    import subprocess
+    exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    try:
+        out = subprocess.run([exe, "--showclocks", "--showpower", "--json"], capture_output=True, text=True,
+                             timeout=20)
+        data = json.loads(out.stdout)
+        card = data[sorted(data)[0]]
+        keep = {k: v for k, v in card.items() if any(t in k.lower() for t in ("sclk", "mclk", "power", "fclk"))}
+        return keep
+    except Exception as e:   # noqa: BLE001
+        return {"unavailable": str(e)[:80]}
 
 
 def cpu_baseline(w, budget_s: float = 15.0):
@@ -260,11 +321,16 @@ def measure_context_distance(n: int = 8192, k: int = 15, stride: int = 16, steps
         ev[i + 1].record(stream)
     torch.cuda.synchronize()
     ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]))
-    # the kernel does one compare and one conditional move per pair of (padded) positions
-    ops = 2.0 * n * n * stride * stride
+    # Eq. 1 is symmetric and its own work is one comparison and one selection per pair of
+    # positions of the k ids of two different contexts: n(n-1)/2 pairs x k^2 positions x 2.  The
+    # kernel fills the whole matrix over the padded stride, i.e. it executes n^2 x stride^2 x 2.
+    useful = 2.0 * (n * (n - 1) / 2.0) * k * k
+    executed = 2.0 * n * n * stride * stride
     res = {"workload": f"context_distance n={n} k={k}", "ms": ms, "pairs_per_s": n * n / (ms * 1e-3),
-           "roofline": {"bound": "alu", "achieved": ops / (ms * 1e-3) / 1e12, "peak": PEAK_INT32_TOPS,
-                        "unit": "Tops/s (int32)", "frac": ops / (ms * 1e-3) / 1e12 / PEAK_INT32_TOPS,
+           "roofline": {"bound": "alu", "achieved": useful / (ms * 1e-3) / 1e12, "peak": PEAK_INT32_TOPS,
+                        "unit": "Tops/s (int32)", "frac": useful / (ms * 1e-3) / 1e12 / PEAK_INT32_TOPS,
+                        "executed_tops": executed / (ms * 1e-3) / 1e12,
+                        "frac_executed": executed / (ms * 1e-3) / 1e12 / PEAK_INT32_TOPS,
                         "traffic": None},
            "write_gbs": n * n * 4 / (ms * 1e-3) / 1e9}
     if cpu:
@@ -352,24 +418,29 @@ def measure_context_dedup(cpu: bool = True):
     return res
 
 
-def measure_mfma_ceiling(iters: int = 100000):
-    """What the matrix pipe of this device sustains on nothing but back-to-back MFMAs, with
-    constant operands and with random-looking ones (the rate depends on operand bit toggling)."""
+def measure_ceilings(iters: int = 100000):
+    """What this device sustains on (a) nothing but back-to-back MFMAs and (b) the attention
+    kernel's instruction mix per MFMA (operand read from LDS, softmax arithmetic) with nothing
+    else in the way, on constant operands and on operands that toggle like N(0,1) samples: the
+    device lowers its clock under a power limit, so the rates depend on the operand bits."""
     import torch
     import paper_2511_03475_amd as cp
     sink = torch.empty(cp.cp_probe_mfma_sink_floats(), dtype=torch.float32, device="cuda:0")
     stream = torch.cuda.current_stream()
     out = {}
-    for name, rnd in (("constant_operands", False), ("random_operands", True)):
-        for _ in range(4):   # ~100 ms of the same load first: steady clock, as for the workloads
-            cp.cp_probe_mfma(rnd, iters, sink, stream)
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        a.record(stream)
-        cp.cp_probe_mfma(rnd, iters, sink, stream)
-        b.record(stream)
-        torch.cuda.synchronize()
-        out[name] = cp.cp_probe_mfma_flops(iters) / (a.elapsed_time(b) * 1e-3) / 1e12
+    for probe, fn in (("mfma_only", cp.cp_probe_mfma), ("attention_mix", cp.cp_probe_mix)):
+        out[probe] = {}
+        for name, kind in (("constant_operands", 0), ("normal_operands", 2)):
+            for _ in range(10):   # ~200 ms of the same load first: steady clock, as for the workloads
+                fn(kind, iters, sink, stream)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            a.record(stream)
+            for _ in range(3):
+                fn(kind, iters, sink, stream)
+            b.record(stream)
+            torch.cuda.synchronize()
+            out[probe][name] = 3.0 * cp.cp_probe_mfma_flops(iters) / (a.elapsed_time(b) * 1e-3) / 1e12
     return out
 
 
@@ -385,8 +456,12 @@ def main():
                     help="untimed run-in of each workload before its warm-up steps (clock transient)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for HBM counters)")
+    ap.add_argument("--operands", choices=("normal", "constant"), default="normal",
+                    help="constant: q, K, V all bf16 1.0 (same work, least power; for the clock account)")
+    ap.add_argument("--splits", type=int, default=0, help="force the split-K factor of the headline workload")
     args = ap.parse_args()
     globals()["SETTLE_MS"] = args.settle_ms
+    globals()["OPERANDS"] = args.operands
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only; use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -411,22 +486,27 @@ def main():
         print(json.dumps(measure_context_distance(steps=args.steps, cpu=not args.no_cpu)))
         return
 
-    w, r, head = measure(args.workload, args.steps, args.warmup)
+    globals()["COPY_CEILING_GBS"] = measure_copy_ceiling()
+    w, r, head = measure(args.workload, args.steps, args.warmup, args.splits)
     cpu = None if args.no_cpu else cpu_baseline(w)
     del r
     torch.cuda.empty_cache()
 
     extra = []
     if not args.no_extra:
-        for name in ("tiny_extend", "rag_fixed", "rag_zipf", "rag_zipf_as_retrieved", "rag_zipf_context_index",
-                     "long_context_32k", "ctx128k_zero_reuse", "ctx128k_reuse", "short_extend_probe",
-                     "chunked_prefill_b8_p16k_e2k",
+        for name in ("tiny_extend", "rag_fixed", "rag_fixed_shared_prefix", "rag_zipf", "rag_zipf_as_retrieved",
+                     "rag_zipf_context_index", "long_context_32k", "long_context_32k:split2", "ctx128k_zero_reuse",
+                     "ctx128k_reuse", "short_extend_probe", "chunked_prefill_b8_p16k_e2k",
                      "decode_b32_p10k", "decode_b32_p10k_e16", "decode_b1_p128k"):
-            if name == args.workload:
+            if name == args.workload and args.splits == 0:
                 extra.append({k: head[k] for k in head})
                 continue
             steps = 5 if name.startswith("ctx128k") or name.startswith("rag_zipf") else 20
-            _, rr, res = measure(name, steps, 2)
+            # "name:splitN": the same workload with the keys split N ways by force (long_context_32k
+            # is timed with the split off, which the plan chooses and which is faster, and on)
+            base, _, forced = name.partition(":split")
+            _, rr, res = measure(base, steps, 2, int(forced) if forced else 0)
+            res["workload"] = name
             extra.append(res)
             del rr
             torch.cuda.empty_cache()
@@ -441,7 +521,8 @@ def main():
     line = {
         "metric": "extend-attention TFLOP/s and % of bf16 MFMA peak at 32k/128k ctx",
         "value": head["tflops_step"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "clock_settle_ms": args.settle_ms, "ms_per_step": head["ms_per_step"],
+        "warmup": args.warmup, "clock_settle_ms": args.settle_ms, "operands": args.operands,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "batch": head["batch"], "q_heads": head["q_heads"],
@@ -450,6 +531,8 @@ def main():
                    "step": "cp_write_kv + cp_extend_attention", "splits": head["splits"]},
         "roofline": roofline_of(args.workload, head),
         "cpu_baseline": cpu,
+        "hbm_copy_ceiling_gbs": COPY_CEILING_GBS,
+        "device_state_after": device_state(),
     }
     if extra:
         line["workloads"] = [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in e.items()
@@ -463,12 +546,11 @@ def main():
         line["context_distance"] = measure_context_distance(cpu=not args.no_cpu)
         line["context_index"] = measure_context_index(cpu=not args.no_cpu)
         line["context_dedup"] = measure_context_dedup(cpu=not args.no_cpu)
-        ceil = measure_mfma_ceiling()
+        ceil = measure_ceilings()
+        line["measured_ceilings_tflops"] = ceil
         if line["roofline"]["bound"] == "mfma":
-            line["roofline"]["measured_mfma_ceiling_tflops"] = ceil
-            line["roofline"]["frac_of_measured_ceiling"] = head["tflops_attn"] / ceil["random_operands"]
-        else:
-            line["measured_mfma_ceiling_tflops"] = ceil
+            line["roofline"]["frac_of_measured_mfma_ceiling"] = head["tflops_attn"] / ceil["mfma_only"]["normal_operands"]
+            line["roofline"]["frac_of_measured_mix_ceiling"] = head["tflops_attn"] / ceil["attention_mix"]["normal_operands"]
     print(json.dumps(line))
 
 

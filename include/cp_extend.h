@@ -88,6 +88,19 @@ size_t cp_workspace_bytes(const cp_shape *shape);
 int32_t cp_num_splits(const cp_shape *shape);
 
 /*
+ * Which kernels cp_extend_attention will launch for this shape (launch planning is host integer
+ * work on the lengths of the batch, the counterpart of the paper's host-side scheduling,
+ * Section 5.2): a pure function of *shape.
+ */
+enum {
+    CP_PLAN_INVALID = 0,
+    CP_PLAN_ROW_TILED = 1,       /* extend_attn_kernel, keys not split */
+    CP_PLAN_ROW_TILED_SPLIT = 2, /* extend_attn_kernel over key ranges + merge_splits_kernel */
+    CP_PLAN_DECODE = 3           /* decode_attn_kernel (a wavefront per key chunk) + merge_splits_kernel */
+};
+int32_t cp_plan_kind(const cp_shape *shape);
+
+/*
  * Extend attention (paper, Section 1: prefill over a prefix cache).  For request r, q head h,
  * g = h / G and extend row i in [0, E_r):
  *     key(j), val(j):  j <  P_r -> row j % PS of head g in page block_table[r][j / PS]

@@ -1,12 +1,18 @@
 /*
  * cp_probe: measurement aids (C ABI).  Not part of the method: these kernels exist so that the
- * benchmark can report, next to the published peak, the rate this very device sustains.
+ * benchmark can report, next to the published peak, the rates this very device sustains.
  *
  * cp_probe_mfma runs nothing but back-to-back v_mfma_f32_32x32x16_bf16 instructions (the
- * instruction the attention kernel is built on) on every SIMD of the device, either on
- * constant operands or on operands whose sign and mantissa bits look random.  The matrix
- * pipe's sustained rate depends on how many operand bits toggle (power), so the second figure
- * is the realistic ceiling for a bf16 kernel working on real data.
+ * instruction the attention kernel is built on) on every SIMD of the device.  The matrix pipe's
+ * sustained rate depends on how many operand bits toggle: the device lowers its clock under a
+ * power limit, so constant operands run at the published rate and random ones do not.
+ *
+ * cp_probe_mix adds what the attention kernel does per MFMA besides the product: the A operand
+ * is read from LDS (16 bytes per lane) and, for every second MFMA, two values go through fma +
+ * exp2, one packed conversion to bf16 and one dot2 row-sum step (per MFMA: 1 exp2, 1 fma, 1/2
+ * cvt, 1/2 dot2 - the attention kernel's softmax per score).  No global loads, LDS writes,
+ * barriers or waits for fresh MFMA results: it is the ceiling of that instruction mix on this
+ * device, in instruction issue and in power.
  */
 #ifndef CP_PROBE_H
 #define CP_PROBE_H
@@ -19,19 +25,30 @@ extern "C" {
 #endif
 
 /*
- * random_operands  0: every operand element is bf16 1.0; 1: sign and mantissa from a hash of
- *                  (workgroup, lane, register), magnitude in [1, 2)
- * iters            loop trips per wavefront, 1 <= iters <= 2^24; each trip issues 8 MFMAs
- * sink             DEVICE float32 [cp_probe_mfma_sink_floats()], written (keeps the work alive)
- * stream           hipStream_t as void*, NULL = default stream
+ * operands   0: every operand element is bf16 1.0; 1: sign and mantissa from a hash of
+ *            (workgroup, lane, register), magnitude in [1, 2); 2: as 1 with the exponent drawn
+ *            from 2^-3 .. 2^1 as well (the spread of N(0,1) samples)
+ * iters      loop trips per wavefront, a multiple of 8 in [8, 2^24]; each trip issues 8 MFMAs
+ * sink       DEVICE float32 [cp_probe_mfma_sink_floats()], written (keeps the work alive)
+ * stream     hipStream_t as void*, NULL = default stream
  *
- * Launches one kernel, asynchronously; the caller times it with events on `stream`.
- * Algorithmic work of the launch: cp_probe_mfma_flops(iters) floating-point operations.
- * Returns 0, -1 (NULL sink), -2 (iters out of range) or -4 (HIP launch error).
+ * Each call launches one kernel (256 workgroups of 8 wavefronts), asynchronously; the caller
+ * times it with events on `stream`.  Algorithmic work of a launch of either kernel:
+ * cp_probe_mfma_flops(iters) floating-point operations (the MFMAs only).
+ * Returns 0, -1 (NULL sink), -2 (iters or operands out of range) or -4 (HIP launch error).
  */
-int cp_probe_mfma(int32_t random_operands, int32_t iters, float *sink, void *stream);
+int cp_probe_mfma(int32_t operands, int32_t iters, float *sink, void *stream);
+int cp_probe_mix(int32_t operands, int32_t iters, float *sink, void *stream);
 size_t cp_probe_mfma_sink_floats(void);
 double cp_probe_mfma_flops(int32_t iters);
+
+/*
+ * Plain device-to-device copy of `bytes` bytes (a multiple of 16; both DEVICE pointers 16-byte
+ * aligned, not overlapping), one kernel, asynchronous on `stream`: the rate HBM gives a kernel
+ * that only reads and writes, to put beside the published peak.  Returns 0, -1 (NULL), -2 (size or
+ * alignment) or -4 (HIP launch error).
+ */
+int cp_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -24,9 +24,9 @@ CP_ERR_ALIGN = -5
 CP_ERR_TABLE = -6
 CP_ERR_LENGTHS = -7
 
-EXPORTS = ("cp_workspace_bytes", "cp_num_splits", "cp_extend_attention", "cp_write_kv",
+EXPORTS = ("cp_workspace_bytes", "cp_num_splits", "cp_plan_kind", "cp_extend_attention", "cp_write_kv",
            "cp_extend_attention_noalloc", "cp_noalloc_scratch_bytes",
-           "cp_status_string", "cp_check_tables", "cp_set_debug_validate", "cp_context_distance", "cp_probe_mfma",
+           "cp_status_string", "cp_check_tables", "cp_set_debug_validate", "cp_context_distance", "cp_probe_mfma", "cp_probe_mix", "cp_probe_copy",
            "cp_probe_mfma_sink_floats", "cp_probe_mfma_flops",
            "cp_index_distinct", "cp_index_build", "cp_index_free", "cp_index_num_contexts",
            "cp_index_num_nodes", "cp_index_aligned", "cp_index_path", "cp_index_leaf", "cp_index_node",
@@ -79,6 +79,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.cp_workspace_bytes.argtypes = [sp]
     lib.cp_num_splits.restype = ctypes.c_int32
     lib.cp_num_splits.argtypes = [sp]
+    lib.cp_plan_kind.restype = ctypes.c_int32
+    lib.cp_plan_kind.argtypes = [sp]
     lib.cp_extend_attention.restype = ctypes.c_int
     lib.cp_extend_attention.argtypes = [vp, vp, vp, vp, i32p, i32p, i32p, vp, vp, sp, vp, ctypes.c_size_t]
     lib.cp_extend_attention_noalloc.restype = ctypes.c_int
@@ -95,6 +97,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.cp_context_distance.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_float, vp, vp]
     lib.cp_probe_mfma.restype = ctypes.c_int
     lib.cp_probe_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
+    lib.cp_probe_mix.restype = ctypes.c_int
+    lib.cp_probe_mix.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
+    lib.cp_probe_copy.restype = ctypes.c_int
+    lib.cp_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.cp_probe_mfma_sink_floats.restype = ctypes.c_size_t
     lib.cp_probe_mfma_sink_floats.argtypes = []
     lib.cp_probe_mfma_flops.restype = ctypes.c_double
@@ -192,6 +198,14 @@ def cp_num_splits(shape: Shape) -> int:
     return int(load_library().cp_num_splits(shape.ref()))
 
 
+PLAN_KERNELS = {1: "extend_attn_kernel", 2: "extend_attn_kernel + merge_splits_kernel",
+                3: "decode_attn_kernel + merge_splits_kernel"}
+
+
+def cp_plan_kind(shape: Shape) -> int:
+    return int(load_library().cp_plan_kind(shape.ref()))
+
+
 def cp_extend_attention(q, k_new, v_new, kv_pages, block_table, prefix_lens, extend_lens, out,
                         stream, shape: Shape, workspace=None, workspace_bytes: int = 0,
                         check: bool = True) -> int:
@@ -251,10 +265,24 @@ def cp_context_distance(contexts, lens, n: int, stride: int, alpha: float, dist,
     return st
 
 
-def cp_probe_mfma(random_operands: bool, iters: int, sink, stream, check: bool = True) -> int:
-    st = load_library().cp_probe_mfma(int(bool(random_operands)), int(iters), _ptr(sink), _stream(stream))
+def cp_probe_mfma(operands: int, iters: int, sink, stream, check: bool = True) -> int:
+    st = load_library().cp_probe_mfma(int(operands), int(iters), _ptr(sink), _stream(stream))
     if check and st != CP_OK:
         raise CpError(st, "cp_probe_mfma")
+    return st
+
+
+def cp_probe_mix(operands: int, iters: int, sink, stream, check: bool = True) -> int:
+    st = load_library().cp_probe_mix(int(operands), int(iters), _ptr(sink), _stream(stream))
+    if check and st != CP_OK:
+        raise CpError(st, "cp_probe_mix")
+    return st
+
+
+def cp_probe_copy(dst, src, nbytes: int, stream, check: bool = True) -> int:
+    st = load_library().cp_probe_copy(_ptr(dst), _ptr(src), int(nbytes), _stream(stream))
+    if check and st != CP_OK:
+        raise CpError(st, "cp_probe_copy")
     return st
 
 

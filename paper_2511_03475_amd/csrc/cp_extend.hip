@@ -1304,6 +1304,14 @@ int32_t cp_num_splits(const cp_shape *shape)
     return make_plan(shape).nsplit;
 }
 
+int32_t cp_plan_kind(const cp_shape *shape)
+{
+    if (validate(shape) != CP_OK) return CP_PLAN_INVALID;
+    const Plan pl = make_plan(shape);
+    if (pl.decode) return CP_PLAN_DECODE;
+    return pl.nsplit > 1 ? CP_PLAN_ROW_TILED_SPLIT : CP_PLAN_ROW_TILED;
+}
+
 size_t cp_workspace_bytes(const cp_shape *shape)
 {
     if (validate(shape) != CP_OK) return 0;

@@ -2,17 +2,22 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 #include "cp_probe.h"
 
 namespace {
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-constexpr int kBlocks = 512;  // two workgroups of four wavefronts per compute unit
-constexpr int kThreads = 256;
+constexpr int kBlocks = 256;  // one workgroup of eight wavefronts per compute unit, as the attention kernel
+constexpr int kThreads = 512;
 constexpr int kMfmaPerTrip = 8;
+constexpr int kLdsVectors = 8192; // 128 KiB of operand data in LDS for the mix probe
 
 __device__ inline unsigned mix(unsigned x)
 {
@@ -23,16 +28,40 @@ __device__ inline unsigned mix(unsigned x)
     x ^= x >> 16;
     return x;
 }
-// two bf16 with random sign and mantissa and the exponent of 1.0
-__device__ inline unsigned random_pair(unsigned seed) { return (mix(seed) & 0x807f807fu) | 0x3f803f80u; }
+// Two bf16 values: kind 0 -> 1.0; kind 1 -> random sign and mantissa, exponent of 1.0; kind 2 ->
+// random sign and mantissa and an exponent drawn from 2^-3 .. 2^1 (the spread of N(0,1) samples)
+__device__ inline unsigned operand_pair(int kind, unsigned seed)
+{
+    if (kind == 0) return 0x3f803f80u;
+    const unsigned r = mix(seed) & 0x807f807fu;
+    if (kind == 1) return r | 0x3f803f80u;
+    const unsigned e0 = 124u + mix(seed * 3u + 1u) % 5u, e1 = 124u + mix(seed * 3u + 2u) % 5u;
+    return r | (e0 << 7) | (e1 << 23);
+}
 
 // Eight independent accumulator tiles per wavefront, so that consecutive MFMAs never wait for
-// each other; the B operand rotates so that the loop cannot be folded.
-template <bool kRandom>
-__global__ __launch_bounds__(kThreads) void mfma_stream_kernel(float *sink, int iters)
+// each other; the B operand rotates so that the loop cannot be folded.  The trip loop is
+// unrolled eight times so that every register index is a constant.
+//
+// kMix adds, per MFMA, what the attention kernel does per MFMA besides the product itself: the A
+// operand comes from LDS (one 16-byte read per lane) and, for every second MFMA, two scores go
+// through fma + exp2, one packed conversion to bf16 and one dot2 row-sum step.  There are no
+// global loads, LDS writes, barriers or dependencies on fresh MFMA results: it is the rate of
+// that instruction mix when nothing else is in its way.
+template <bool kMix>
+__global__ __launch_bounds__(kThreads) void mfma_stream_kernel(float *sink, int iters, int kind)
 {
+    __shared__ __attribute__((aligned(16))) u32x4 lds[kMix ? kLdsVectors : 1];
     f32x16 acc[kMfmaPerTrip];
     u32x4 a[kMfmaPerTrip], b[kMfmaPerTrip];
+    if (kMix) {
+        for (int i = threadIdx.x; i < kLdsVectors; i += kThreads) {
+            u32x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = operand_pair(kind, (unsigned)i * 4u + e + blockIdx.x * 77777u);
+            lds[i] = v;
+        }
+    }
 #pragma unroll
     for (int i = 0; i < kMfmaPerTrip; ++i) {
 #pragma unroll
@@ -40,23 +69,69 @@ __global__ __launch_bounds__(kThreads) void mfma_stream_kernel(float *sink, int 
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const unsigned seed = (blockIdx.x * kThreads + threadIdx.x) * 64u + i * 8u + e;
-            a[i][e] = kRandom ? random_pair(seed) : 0x3f803f80u;
-            b[i][e] = kRandom ? random_pair(seed + 4u) : 0x3f803f80u;
+            a[i][e] = operand_pair(kind, seed);
+            b[i][e] = operand_pair(kind, seed + 4u);
         }
     }
-    for (int it = 0; it < iters; ++it) {
+    __syncthreads();
+    float psum = 0.f, keep = 0.f;
+    const float c = 0.127f, m = kind == 0 ? 0.f : 0.37f;
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    const int lane_off = (threadIdx.x & 63) + (threadIdx.x >> 6) * 1024;
+    for (int it = 0; it < iters; it += 8) {
 #pragma unroll
-        for (int i = 0; i < kMfmaPerTrip; ++i)
-            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]),
-                                                             __builtin_bit_cast(bf16x8, b[(i + it) & 7]), acc[i],
-                                                             0, 0, 0);
+        for (int u = 0; u < 8; ++u) {
+#pragma unroll
+            for (int i = 0; i < kMfmaPerTrip; ++i) {
+                u32x4 av = a[i];
+                if (kMix) av = lds[lane_off + ((i + u * 8) & 15) * 64];
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av),
+                                                                 __builtin_bit_cast(bf16x8, b[(i + u) & 7]), acc[i],
+                                                                 0, 0, 0);
+                if (kMix && (i & 1)) {
+                    f32x2 x; // "scores": elements of an accumulator that was written four MFMAs ago
+                    x[0] = __builtin_amdgcn_exp2f(fmaf(acc[(i + 4) & 7][u], c, -m));
+                    x[1] = __builtin_amdgcn_exp2f(fmaf(acc[(i + 4) & 7][u + 8], c, -m));
+                    const bf16x2 y = __builtin_convertvector(x, bf16x2);
+                    psum = __builtin_amdgcn_fdot2_f32_bf16(y, ones, psum, false);
+                    keep += x[0];
+                }
+            }
+        }
     }
-    float r = 0.f;
+    float r = psum + keep;
 #pragma unroll
     for (int i = 0; i < kMfmaPerTrip; ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) r += acc[i][v];
     sink[blockIdx.x * kThreads + threadIdx.x] = r;
+}
+
+// Plain device copy: every thread moves four 16-byte pieces per step (four loads in flight before
+// the first store), streaming hints on both sides: what HBM gives a kernel that does nothing else.
+constexpr int kCopyUnroll = 4;
+__global__ __launch_bounds__(256) void copy_kernel(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * 256 * kCopyUnroll;
+    for (size_t base = (size_t)blockIdx.x * 256 * kCopyUnroll + threadIdx.x; base < n; base += stride) {
+        u32x4 v[kCopyUnroll];
+#pragma unroll
+        for (int u = 0; u < kCopyUnroll; ++u)
+            if (base + u * 256 < n) v[u] = __builtin_nontemporal_load(src + base + u * 256);
+#pragma unroll
+        for (int u = 0; u < kCopyUnroll; ++u)
+            if (base + u * 256 < n) __builtin_nontemporal_store(v[u], dst + base + u * 256);
+    }
+}
+
+int launch(bool with_mix, int32_t operands, int32_t iters, float *sink, void *stream)
+{
+    if (!sink) return -1;
+    if (iters < 8 || iters > (1 << 24) || iters % 8 != 0 || operands < 0 || operands > 2) return -2;
+    hipStream_t hs = (hipStream_t)stream;
+    if (with_mix) hipLaunchKernelGGL(mfma_stream_kernel<true>, dim3(kBlocks), dim3(kThreads), 0, hs, sink, iters, operands);
+    else hipLaunchKernelGGL(mfma_stream_kernel<false>, dim3(kBlocks), dim3(kThreads), 0, hs, sink, iters, operands);
+    return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
 } // namespace
@@ -69,12 +144,23 @@ extern "C" double cp_probe_mfma_flops(int32_t iters)
     return (double)kBlocks * (kThreads / 64) * (double)iters * kMfmaPerTrip * (2.0 * 32 * 32 * 16);
 }
 
-extern "C" int cp_probe_mfma(int32_t random_operands, int32_t iters, float *sink, void *stream)
+extern "C" int cp_probe_mfma(int32_t operands, int32_t iters, float *sink, void *stream)
 {
-    if (!sink) return -1;
-    if (iters < 1 || iters > (1 << 24)) return -2;
-    hipStream_t hs = (hipStream_t)stream;
-    if (random_operands) hipLaunchKernelGGL(mfma_stream_kernel<true>, dim3(kBlocks), dim3(kThreads), 0, hs, sink, iters);
-    else hipLaunchKernelGGL(mfma_stream_kernel<false>, dim3(kBlocks), dim3(kThreads), 0, hs, sink, iters);
+    return launch(false, operands, iters, sink, stream);
+}
+
+extern "C" int cp_probe_mix(int32_t operands, int32_t iters, float *sink, void *stream)
+{
+    return launch(true, operands, iters, sink, stream);
+}
+
+extern "C" int cp_probe_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src) return -1;
+    if (bytes == 0 || bytes % 16 != 0 || (uintptr_t)dst % 16 != 0 || (uintptr_t)src % 16 != 0) return -2;
+    const size_t n = bytes / 16;
+    const size_t per_block = 256 * kCopyUnroll;
+    const unsigned blocks = (unsigned)std::min<size_t>((n + per_block - 1) / per_block, 256u * 16u);
+    hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (u32x4 *)dst, (const u32x4 *)src, n);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }

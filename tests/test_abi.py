@@ -81,6 +81,16 @@ def test_decode_shaped_calls_get_a_wavefront_level_plan(lib):
     assert cp.cp_num_splits(_shape([10240] * 64, [17] * 64)) == 1
 
 
+def test_plan_kind_names_the_kernels_that_will_run(lib):
+    assert cp.cp_plan_kind(_shape([24576] * 4, [8192] * 4, Hq=64)) == 1          # row-tiled, unsplit
+    assert cp.cp_plan_kind(_shape([24576] * 4, [8192] * 4, Hq=64, splits=2)) == 2
+    assert cp.cp_plan_kind(_shape([10240], [128])) == 2                           # few workgroups: split
+    assert cp.cp_plan_kind(_shape([10240] * 32, [1] * 32)) == 3                   # decode-shaped
+    assert cp.cp_plan_kind(_shape([10240] * 32, [1] * 32, splits=1)) == 1
+    assert cp.cp_plan_kind(_shape([32], [32], D=64)) == 0
+    assert set(cp.PLAN_KERNELS) == {1, 2, 3}
+
+
 def test_invalid_shapes_are_rejected_on_the_host(lib):
     bad = [
         _shape([32], [32], Hq=4, Hkv=3),           # Hq % Hkv != 0

@@ -88,12 +88,12 @@ def _bench_workload(name):
 
 
 @pytest.mark.parametrize("name,q_block", [("short_extend_probe", 64), ("rag_zipf_as_retrieved", 1024),
-                                          ("rag_zipf_context_index", 1024)])
+                                          ("rag_zipf_context_index", 1024), ("rag_fixed_shared_prefix", 128)])
 def test_other_timed_extend_shapes_sampled(H, name, q_block):
     """Shapes that bench.py times beside the five configs, at the size timed: the short-extend
     probe (32 requests x 128 new tokens over 10240 cached, two q heads packed per workgroup) and
     the Zipf batch in the other two block orders (as retrieved; aligned and scheduled by the
-    context index)."""
+    context index), and the fixed-reuse batch with all eight requests on one shared cached prefix."""
     w = _bench_workload(name)
     rows = W.sample_rows(w, 21, q_block=q_block, edge=4, seams=2)
     _sampled(H, w, rows, name)

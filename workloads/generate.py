@@ -202,12 +202,15 @@ def config1_tiny(seed: int = BASE_SEED + 1) -> Workload:
 
 def config2_rag_fixed(seed: int = BASE_SEED + 2, batch: int = 8, block: int = 1024,
                       cached_blocks: int = 6, total_blocks: int = 8, query: int = 256,
-                      Hq: int = 32, Hkv: int = 8, cached_region_pages: int = 4096) -> Workload:
+                      Hq: int = 32, Hkv: int = 8, cached_region_pages: int = 4096,
+                      shared_prefix: bool = False) -> Workload:
     """RAG batch with fixed reuse.
 
     Cached pages are a seeded permutation inside a region of `cached_region_pages`
     pages; the destination pages of the extend part come from a seeded permutation
     of a second region appended after it (the stated pool cannot hold both).
+    shared_prefix: every request's cached prefix is the same physical pages (the paper's
+    multi-session case, Section 3.2: sessions that share one cached context).
     """
     rngs = _streams(seed)
     P = cached_blocks * block
@@ -220,9 +223,9 @@ def config2_rag_fixed(seed: int = BASE_SEED + 2, batch: int = 8, block: int = 10
     perm_e = cached_region_pages + rngs[4].permutation(batch * ep)
     table = np.full((batch, pp + ep), -1, dtype=np.int32)
     for r in range(batch):
-        table[r, :pp] = perm_c[r * pp:(r + 1) * pp]
+        table[r, :pp] = perm_c[:pp] if shared_prefix else perm_c[r * pp:(r + 1) * pp]
         table[r, pp:pp + ep] = perm_e[r * ep:(r + 1) * ep]
-    return _assemble("rag_fixed", seed, Hq, Hkv, [P] * batch, [E] * batch, table,
+    return _assemble("rag_fixed_shared_prefix" if shared_prefix else "rag_fixed", seed, Hq, Hkv, [P] * batch, [E] * batch, table,
                      cached_region_pages + batch * ep, rngs=rngs)
 
 
