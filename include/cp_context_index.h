@@ -103,6 +103,9 @@ int cp_index_search(const cp_index *index, const int32_t *ids, int32_t len, int3
  * Search, align and store a new context (it becomes stored context cp_index_num_contexts()-1).
  * aligned   out [len]: the context to run, a permutation of ids
  * path      out: its search path; cap entries available, path_len receives the length
+ * The index is changed only when 0 is returned.  The path of the stored context has at most one
+ * entry more than the path cp_index_search reports for the same ids; when cap is below that
+ * bound the call returns -2 with the bound in path_len and stores nothing.
  */
 int cp_index_insert(cp_index *index, const int32_t *ids, int32_t len, int32_t *aligned,
                     int32_t *path, int32_t cap, int32_t *path_len);

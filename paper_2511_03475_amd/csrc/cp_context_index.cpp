@@ -443,6 +443,12 @@ extern "C" int cp_index_insert(cp_index *index, const int32_t *ids, int32_t len,
     std::vector<Node> &nodes = index->nodes;
     std::vector<int32_t> p;
     int32_t node = index->search(C, p);
+    // Nothing is changed before the outputs are known to fit: the stored leaf ends up at most
+    // one level below the matched node, so its path has at most p.size() + 1 entries.  A caller
+    // that gets -2 can come back with a larger buffer and finds the index as it was.
+    if (path_len) *path_len = (int32_t)p.size() + 1;
+    if ((int64_t)p.size() + 1 > (int64_t)cap) return -2;
+    if (!path) return -1;
     int32_t leaf = -1;
     if (nodes[node].leaf && nodes[node].docs == align_to(nodes[nodes[node].parent].docs, C)) {
         leaf = node; // identical context
