@@ -2,8 +2,9 @@
  * cp_context_distance: pairwise distance between contexts for the context index (C ABI).
  *
  * The paper builds its context index by hierarchical clustering over pairwise context
- * distances (Section 4.1, "Index creation"; Algorithm "Context Index Construction", phase 1:
- * "pairwise distances ... GPU or CPU") with the distance of Eq. 1:
+ * distances (Section 4.1, "Index creation"; first phase of the appendix algorithm "Context Index
+ * Construction via Hierarchical Clustering", which the paper runs on a GPU or on CPUs) with the
+ * distance of Eq. 1:
  *
  *     d_ij = 1 - |S_ij| / max(|C_i|, |C_j|) + alpha * (sum_{k in S_ij} |p_i(k) - p_j(k)|) / |S_ij|
  *

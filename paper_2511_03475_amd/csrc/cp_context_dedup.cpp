@@ -45,10 +45,12 @@ void chunk_ends(const uint8_t *bytes, int64_t len, uint64_t modulus, std::vector
 
 } // namespace
 
+// State of one conversation: which blocks earlier turns brought, and for every sub-block content
+// (by hash) the block that brought it first.
 struct cp_dedup {
     uint64_t modulus = 1;
-    std::unordered_set<int32_t> seen_blocks;
-    std::unordered_map<uint64_t, int32_t> seen_subblocks;
+    std::unordered_set<int32_t> earlier_turn_blocks;
+    std::unordered_map<uint64_t, int32_t> owner_of_hash;
 };
 
 extern "C" uint64_t cp_dedup_hash(const uint8_t *bytes, int64_t len)
@@ -95,41 +97,39 @@ extern "C" int cp_dedup_turn(cp_dedup *conv, const int32_t *ids, const uint8_t *
         if (offsets[i] < 0 || offsets[i + 1] < offsets[i]) return -2;
     if (n > 0 && offsets[n] > 0 && !bytes) return -1;
 
-    // work on a copy of the hash table so that a too-small output buffer leaves the state as it was
-    std::unordered_map<uint64_t, int32_t> table = conv->seen_subblocks;
+    // Pass over whole blocks: a block that an earlier turn of the conversation brought is
+    // answered by a reference and not looked into.
+    std::vector<int32_t> to_cut;
+    for (int32_t i = 0; i < n; ++i) {
+        block_ref[i] = conv->earlier_turn_blocks.count(ids[i]) ? 1 : 0;
+        if (!block_ref[i]) to_cut.push_back(i);
+    }
+    // Pass over the sub-blocks of the others, in order: content that a different block owns
+    // becomes a reference to that block, anything else is kept and owned from now on.  The
+    // ownership table is edited on a copy, so that a too small output buffer leaves the
+    // conversation as it was.
+    std::unordered_map<uint64_t, int32_t> owners = conv->owner_of_hash;
     std::vector<cp_dedup_sub> out;
     std::vector<int64_t> ends;
     int64_t kept = 0;
-    for (int32_t i = 0; i < n; ++i) {
-        const int32_t b = ids[i];
-        if (conv->seen_blocks.count(b)) {
-            block_ref[i] = 1;
-            continue;
-        }
-        block_ref[i] = 0;
+    for (int32_t i : to_cut) {
         const uint8_t *text = bytes + offsets[i];
         chunk_ends(text, offsets[i + 1] - offsets[i], conv->modulus, ends);
-        int64_t at = 0;
+        int64_t begin = 0;
         for (int64_t end : ends) {
-            const uint64_t f = fnv1a(text + at, end - at);
-            auto it = table.find(f);
-            cp_dedup_sub s{i, -1, at, end};
-            if (it != table.end() && it->second != b) {
-                s.ref = it->second;
-            } else {
-                table[f] = b;
-                kept += end - at;
-            }
-            out.push_back(s);
-            at = end;
+            const auto claim = owners.emplace(fnv1a(text + begin, end - begin), ids[i]);
+            const int32_t owner = claim.first->second; // this block itself when the content is new
+            out.push_back(cp_dedup_sub{i, owner == ids[i] ? -1 : owner, begin, end});
+            if (owner == ids[i]) kept += end - begin;
+            begin = end;
         }
     }
     *subs_count = (int32_t)out.size();
     if ((int32_t)out.size() > subs_cap) return -2;
     if (!out.empty() && !subs) return -1;
     for (size_t k = 0; k < out.size(); ++k) subs[k] = out[k];
-    conv->seen_subblocks.swap(table);
-    for (int32_t i = 0; i < n; ++i) conv->seen_blocks.insert(ids[i]);
+    conv->owner_of_hash.swap(owners);
+    conv->earlier_turn_blocks.insert(ids, ids + n);
     if (kept_bytes) *kept_bytes = kept;
     return 0;
 }
