@@ -629,10 +629,15 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
 }
 
 // out[row, head, :] = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max_s m_s).
-// One workgroup per (row, head): eight groups of 32 threads take the splits s = g, g + 8, ...
-// (4 consecutive d per thread), then the eight partial sums are added in a fixed order, so the
-// result is reproducible.  Entries with l_s = 0 (empty splits) are skipped.
-constexpr int kMergeGroups = 8;
+// Entries with l_s = 0 (empty splits) are skipped.  Two forms, chosen by the number of splits; in
+// both every sum runs in a fixed order, so the result is reproducible.
+//
+// Many splits: one workgroup per (row, head).  kMergeGroups groups of 32 threads take the splits
+// s = g, g + kMergeGroups, ... (at most kMergePerGroup each; 4 consecutive d per thread), then the
+// partial sums of the groups are added in group order.
+constexpr int kMergeGroups = 32;
+constexpr int kMergePerGroup = 8; // splits per group: up to 256 partial results in all
+constexpr int kMergeFewSplits = 8; // up to this many splits the second form is used
 __global__ __launch_bounds__(32 * kMergeGroups) void merge_splits_kernel(const float *__restrict__ part_o,
                                                                           const float *__restrict__ part_ml,
                                                                           uint16_t *__restrict__ out,
@@ -644,15 +649,24 @@ __global__ __launch_bounds__(32 * kMergeGroups) void merge_splits_kernel(const f
     const int64_t rh = blockIdx.x;
     const int g = threadIdx.x >> 5, t = threadIdx.x & 31;
     const int d4 = t * 4;
-    // maximum over all splits: every thread scans a strided share, then a reduction inside the
-    // group of 32 (lanes of one wavefront) and across groups through LDS
-    float m = -INFINITY;
-    for (int s = threadIdx.x; s < nsplit; s += 32 * kMergeGroups) {
-        const float *ml = part_ml + ((int64_t)s * n_rh + rh) * 2;
-        if (ml[1] > 0.f) m = fmaxf(m, ml[0]);
-    }
+    // all loads of the group first (one round of memory latency), then the arithmetic
+    float ms[kMergePerGroup], ls[kMergePerGroup];
+    f32x4 x[kMergePerGroup];
 #pragma unroll
-    for (int off = 16; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 32));
+    for (int i = 0; i < kMergePerGroup; ++i) {
+        const int s = g + i * kMergeGroups;
+        const bool on = s < nsplit;
+        const f32x2 ml = on ? *reinterpret_cast<const f32x2 *>(part_ml + ((int64_t)s * n_rh + rh) * 2) : f32x2{0.f, 0.f};
+        ms[i] = ml[0];
+        ls[i] = ml[1];
+        x[i] = on ? *reinterpret_cast<const f32x4 *>(part_o + ((int64_t)s * n_rh + rh) * kD + d4) : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    // maximum over all splits: inside the group every thread holds the same values; across groups
+    // through LDS
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < kMergePerGroup; ++i)
+        if (ls[i] > 0.f) m = fmaxf(m, ms[i]);
     if (t == 0) s_max[g] = m;
     __syncthreads();
     float m_star = s_max[0];
@@ -661,16 +675,13 @@ __global__ __launch_bounds__(32 * kMergeGroups) void merge_splits_kernel(const f
 
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float denom = 0.f;
-    for (int s = g; s < nsplit; s += kMergeGroups) {
-        const float *ml = part_ml + ((int64_t)s * n_rh + rh) * 2;
-        const float ls = ml[1];
-        if (ls > 0.f) {
-            const float w = fast_exp2(ml[0] - m_star);
-            const f32x4 x = *reinterpret_cast<const f32x4 *>(part_o + ((int64_t)s * n_rh + rh) * kD + d4);
-            acc += x * w;
-            denom += ls * w;
+#pragma unroll
+    for (int i = 0; i < kMergePerGroup; ++i)
+        if (ls[i] > 0.f) {
+            const float w = fast_exp2(ms[i] - m_star);
+            acc += x[i] * w;
+            denom += ls[i] * w;
         }
-    }
     s_acc[g][t] = acc;
     if (t == 0) s_den[g] = denom;
     __syncthreads();
@@ -680,6 +691,46 @@ __global__ __launch_bounds__(32 * kMergeGroups) void merge_splits_kernel(const f
         acc += s_acc[i][t];
         denom += s_den[i];
     }
+    const float inv = denom > 0.f ? 1.f / denom : 0.f;
+    bf16x4 y;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] = (__bf16)(acc[e] * inv);
+    *reinterpret_cast<bf16x4 *>(out + rh * kD + d4) = y;
+}
+
+// Few splits: a group of 32 threads per (row, head), eight of them per workgroup, each walking
+// over its splits in order with all loads of a pass in flight together.
+template <int kSplits>
+__global__ __launch_bounds__(256) void merge_few_splits_kernel(const float *__restrict__ part_o,
+                                                               const float *__restrict__ part_ml,
+                                                               uint16_t *__restrict__ out, int64_t n_rh, int nsplit)
+{
+    const int64_t rh = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);
+    if (rh >= n_rh) return;
+    const int d4 = (threadIdx.x & 31) * 4;
+    float ms[kSplits], ls[kSplits];
+    f32x4 x[kSplits];
+#pragma unroll
+    for (int s = 0; s < kSplits; ++s) {
+        const bool on = s < nsplit;
+        const f32x2 ml = on ? *reinterpret_cast<const f32x2 *>(part_ml + ((int64_t)s * n_rh + rh) * 2) : f32x2{0.f, 0.f};
+        ms[s] = ml[0];
+        ls[s] = ml[1];
+        x[s] = on ? *reinterpret_cast<const f32x4 *>(part_o + ((int64_t)s * n_rh + rh) * kD + d4) : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    float m_star = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < kSplits; ++s)
+        if (ls[s] > 0.f) m_star = fmaxf(m_star, ms[s]);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float denom = 0.f;
+#pragma unroll
+    for (int s = 0; s < kSplits; ++s)
+        if (ls[s] > 0.f) {
+            const float w = fast_exp2(ms[s] - m_star);
+            acc += x[s] * w;
+            denom += ls[s] * w;
+        }
     const float inv = denom > 0.f ? 1.f / denom : 0.f;
     bf16x4 y;
 #pragma unroll
@@ -708,6 +759,8 @@ constexpr int kDecPitchV = 320;
 constexpr int kDecLdsK = 32 * kDecPitchK;
 constexpr int kDecLdsPerWave = kDecLdsK + 32 * kDecPitchV;
 constexpr int kDecMaxChunks = 256;      // key chunks (= partial results) per (request, KV head)
+static_assert(kDecMaxChunks <= kMergeGroups * kMergePerGroup && kMaxSplits <= kMergeGroups * kMergePerGroup,
+              "the merge kernel holds all partial results of a row in registers");
 
 struct DecBlock { // one block of 32 keys as loaded: piece i is row (lane / 16) + 4 i, chunk lane % 16
     u32x4 k[8];
@@ -1153,6 +1206,24 @@ Plan make_plan(const cp_shape *s)
     return pl;
 }
 
+
+// Launches the merge of nsplit partial results for n_rh (row, head) pairs.
+void launch_merge(const AttnParams &p, int nsplit, hipStream_t hs)
+{
+    const int64_t n_rh = (int64_t)p.T * p.Hq;
+    if (nsplit <= kMergeFewSplits) {
+        const dim3 grid((unsigned)((n_rh + 7) / 8));
+        if (nsplit <= 4)
+            hipLaunchKernelGGL(merge_few_splits_kernel<4>, grid, dim3(256), 0, hs, p.part_o, p.part_ml, p.out, n_rh, nsplit);
+        else
+            hipLaunchKernelGGL(merge_few_splits_kernel<kMergeFewSplits>, grid, dim3(256), 0, hs, p.part_o, p.part_ml,
+                               p.out, n_rh, nsplit);
+    } else {
+        hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)n_rh), dim3(32 * kMergeGroups), 0, hs, p.part_o,
+                           p.part_ml, p.out, n_rh, nsplit);
+    }
+}
+
 size_t workspace_for(const cp_shape *s, const Plan &pl)
 {
     if (pl.nsplit <= 1) return 0;
@@ -1385,9 +1456,7 @@ int run_attention(const void *q, const void *k_new, const void *v_new, const voi
         p.part_ml = reinterpret_cast<float *>(static_cast<char *>(workspace) + o_bytes);
         hipLaunchKernelGGL(decode_attn_kernel, dim3((unsigned)(dec_units / kDecWaves)), dim3(kDecWaves * 64), 0, hs, p);
         if (hipGetLastError() != hipSuccess) return CP_ERR_LAUNCH;
-        const int64_t n_rh = (int64_t)p.T * p.Hq;
-        hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)n_rh), dim3(32 * kMergeGroups), 0, hs,
-                           p.part_o, p.part_ml, p.out, n_rh, pl.nsplit);
+        launch_merge(p, pl.nsplit, hs);
         return hipGetLastError() == hipSuccess ? CP_OK : CP_ERR_LAUNCH;
     }
     if (!allow_large_lds()) return CP_ERR_LAUNCH;
@@ -1399,9 +1468,7 @@ int run_attention(const void *q, const void *k_new, const void *v_new, const voi
         p.part_ml = reinterpret_cast<float *>(static_cast<char *>(workspace) + o_bytes);
         hipLaunchKernelGGL(extend_attn_kernel<true>, grid, block, kLdsBytes, hs, p);
         if (hipGetLastError() != hipSuccess) return CP_ERR_LAUNCH;
-        const int64_t n_rh = (int64_t)p.T * p.Hq;
-        hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)n_rh), dim3(32 * kMergeGroups), 0, hs,
-                           p.part_o, p.part_ml, p.out, n_rh, pl.nsplit);
+        launch_merge(p, pl.nsplit, hs);
     } else {
         hipLaunchKernelGGL(extend_attn_kernel<false>, grid, block, kLdsBytes, hs, p);
     }
