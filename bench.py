@@ -30,10 +30,12 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # valid only for the kernel source they were taken with: reported as null as soon as that source
 # changes.  They are not measured by this script.
 TRAFFIC = {
-    "source_sha256_16": "345b83203334e8fd",
-    "from": "profiles/extend_attn_kernel_long_context_32k.md, profiles/decode_attn_kernel_decode_b32_p10k.md",
-    "long_context_32k": (2130348 * 2.0 + 524288) * 1024.0,      # extend_attn_kernel
-    "decode_b32_p10k": (656159 * 2.0 + 4161) * 1024.0,          # decode_attn_kernel
+    "source_sha256_16": "0fc3ec2284b78bb3",
+    "from": "profiles/extend_attn_kernel_long_context_32k.md, decode_attn_kernel_decode_b32_p10k.md, "
+            "extend_attn_kernel_short_extend_probe.md",
+    "long_context_32k": (2130340 * 2.0 + 524289) * 1024.0,      # extend_attn_kernel
+    "decode_b32_p10k": (656155 * 2.0 + 4160) * 1024.0,          # decode_attn_kernel
+    "short_extend_probe": (680744 * 2.0 + 32768) * 1024.0,      # extend_attn_kernel (out = 32 MiB)
 }
 
 
@@ -252,18 +254,22 @@ def measure_copy_ceiling(nbytes: int = 1 << 30, steps: int = 20) -> float:
 
 
 def device_state() -> dict:
-    """Clocks and power as rocm-smi prints them right after the timed runs (a child process;
-    best effort: an empty dict when the tool is missing or refuses)."""
+    """Clocks and power as rocm-smi prints them right after the timed runs.  The tool runs as a
+    child process, started with this interpreter (no launcher hop); skipped under a profiler,
+    whose preloaded library would initialise the GPU in the child as well.  Best effort: a note
+    instead of figures when the tool is missing or refuses."""
     import shutil
     import subprocess
+    if any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ) or "rocprof" in os.environ.get("LD_PRELOAD", ""):
+        return {"skipped": "running under a profiler"}
     exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
     try:
-        out = subprocess.run([exe, "--showclocks", "--showpower", "--json"], capture_output=True, text=True,
-                             timeout=20)
+        exe = os.path.realpath(exe)
+        out = subprocess.run([sys.executable, exe, "--showclocks", "--showpower", "--json"], capture_output=True,
+                             text=True, timeout=20)
         data = json.loads(out.stdout)
         card = data[sorted(data)[0]]
-        keep = {k: v for k, v in card.items() if any(t in k.lower() for t in ("sclk", "mclk", "power", "fclk"))}
-        return keep
+        return {k: v for k, v in card.items() if any(t in k.lower() for t in ("sclk", "mclk", "power", "fclk"))}
     except Exception as e:   # noqa: BLE001
         return {"unavailable": str(e)[:80]}
 
