@@ -89,3 +89,22 @@ def test_debug_mode_refuses_to_launch_on_a_bad_table(case):
     assert (case.pool_bits() == pool_before).all()
     good.attention()
     assert (good.out_bits() == with_debug).all()
+
+
+def test_batches_beyond_one_grid_dimension_are_checked_in_full():
+    """70000 one-token requests: the check walks the batch in pieces of 65535 requests; an offence in
+    the second piece is found and reported with its request number."""
+    B = 70000
+    table = np.arange(B, dtype=np.int32).reshape(B, 1)
+    zeros, ones = np.zeros(B, np.int32), np.ones(B, np.int32)
+    sh = cp.Shape(B, 2, 1, 128, 16, B, 1, zeros, ones, 0.1)
+    dev = lambda a: torch.from_numpy(a).to("cuda:0")
+    s = torch.cuda.current_stream()
+    st, info = cp.cp_check_tables(dev(table), dev(zeros), dev(ones), s, sh, check=False)
+    assert st == cp.CP_OK
+    table[66000, 0] = B
+    st, info = cp.cp_check_tables(dev(table), dev(zeros), dev(ones), s, sh, check=False)
+    assert st == cp.CP_ERR_TABLE and info == [66000, 0, B]
+    table[123, 0] = -5
+    st, info = cp.cp_check_tables(dev(table), dev(zeros), dev(ones), s, sh, check=False)
+    assert st == cp.CP_ERR_TABLE and info == [123, 0, -5]
