@@ -74,7 +74,7 @@ __global__ __launch_bounds__(kThreads) void mfma_stream_kernel(float *sink, int 
         }
     }
     __syncthreads();
-    float psum = 0.f, keep = 0.f;
+    float psum = 0.f;
     const float c = 0.127f, m = kind == 0 ? 0.f : 0.37f;
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
     const int lane_off = (threadIdx.x & 63) + (threadIdx.x >> 6) * 1024;
@@ -94,12 +94,11 @@ __global__ __launch_bounds__(kThreads) void mfma_stream_kernel(float *sink, int 
                     x[1] = __builtin_amdgcn_exp2f(fmaf(acc[(i + 4) & 7][u + 8], c, -m));
                     const bf16x2 y = __builtin_convertvector(x, bf16x2);
                     psum = __builtin_amdgcn_fdot2_f32_bf16(y, ones, psum, false);
-                    keep += x[0];
                 }
             }
         }
     }
-    float r = psum + keep;
+    float r = psum;
 #pragma unroll
     for (int i = 0; i < kMfmaPerTrip; ++i)
 #pragma unroll
