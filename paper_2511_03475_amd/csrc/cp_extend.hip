@@ -1,10 +1,12 @@
 // cp_extend: prefix-cached "extend" prefill attention over a paged KV cache for gfx950.
 //
-// Three kernels behind the C ABI of cp_extend.h:
+// Kernels behind the C ABI of cp_extend.h:
 //   write_kv_kernel       cache append (paper, Section 1: the prefix cache stores prior K/V)
 //   extend_attn_kernel    suffix rows attend to cached prefix pages + their own K/V
 //                         (paper, Section 1 / Section 2.1: prefill over a prefix cache)
-//   merge_splits_kernel   combines split-K partial results
+//   decode_attn_kernel    the same for calls with few rows per KV head (a wavefront per key chunk)
+//   merge_splits_kernel, merge_few_splits_kernel   combine partial results over key ranges
+//   check_tables_kernel   optional check of block_table against the pool size
 //
 // Attention kernel layout.  One workgroup = 8 wavefronts = 256 query rows of one q head; each
 // wavefront owns 32 rows.  Keys are streamed in tiles of 64 through LDS.  Scores are computed
