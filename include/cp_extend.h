@@ -51,7 +51,8 @@ enum {
     CP_OK = 0,
     CP_ERR_NULL = -1,      /* a required pointer is NULL */
     CP_ERR_SHAPE = -2,     /* unsupported or inconsistent shape (see cp_shape) */
-    CP_ERR_WORKSPACE = -3, /* workspace missing, too small or misaligned */
+    CP_ERR_WORKSPACE = -3, /* workspace missing, too small or misaligned; or, for the entry point
+                              without a workspace, a shape that needs more than the library holds */
     CP_ERR_LAUNCH = -4,    /* the HIP runtime reported an error */
     CP_ERR_ALIGN = -5,     /* a device pointer is not aligned as required */
     CP_ERR_TABLE = -6,     /* check: a block_table entry in use lies outside [0, num_pages) */

@@ -1362,7 +1362,9 @@ const char *cp_status_string(int status)
     case CP_OK: return "ok";
     case CP_ERR_NULL: return "a required pointer is NULL";
     case CP_ERR_SHAPE: return "unsupported or inconsistent shape";
-    case CP_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
+    case CP_ERR_WORKSPACE:
+        return "workspace missing, too small or misaligned (cp_extend_attention_noalloc: the shape needs more "
+               "than the library's own scratch)";
     case CP_ERR_LAUNCH: return "HIP launch error";
     case CP_ERR_ALIGN: return "a device pointer is not aligned as required";
     case CP_ERR_TABLE: return "block_table holds a page id outside [0, num_pages)";
