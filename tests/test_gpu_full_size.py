@@ -156,3 +156,38 @@ def test_needle_hits_every_page_at_128k(H):
     pick = np.sort(rng.choice(len(rows), size=6, replace=False))
     want = oracle.attention_of(w, rows=rows[pick].astype(np.int32))
     assert np.abs(want - vals[targets[pick]][:, None, :]).max() < 1e-6
+
+
+@pytest.mark.parametrize("which", ["long_context_32k", "ctx128k_reuse"])
+def test_full_size_closed_forms_on_every_row(H, which):
+    """Two properties that hold at any size and need no sampled oracle, checked on EVERY row and
+    head of the 32k workload (4 requests, 64/8 heads, P=24576, E=8192) and of the 128k reuse run
+    (P=114688, E=16384): q = 0 makes all scores equal, so row i is the mean of the values of keys
+    0 .. P+i of its KV head (a running mean, computed here in fp64 from the same bits); V = 1 makes
+    every output 1."""
+    w = W.config4_long_context() if which == "long_context_32k" else W.config5_128k(True)
+    G = w.num_q_heads // w.num_kv_heads
+    q_saved = w.q.copy()
+    w.q[:] = 0
+    got = bf16_bits_to_f32(H.gpu_attention(w)).astype(np.float64)            # [T, Hq, D]
+    cu = w.cu_extend
+    worst = 0.0
+    for r in range(w.batch):
+        P, E = int(w.prefix_lens[r]), int(w.extend_lens[r])
+        pages = w.block_table[r, :P // 16]
+        vp = bf16_bits_to_f32(w.kv_pages[pages, 1]).astype(np.float64)       # [pages, Hkv, 16, D]
+        vp = vp.transpose(0, 2, 1, 3).reshape(P, w.num_kv_heads, 128)
+        vn = bf16_bits_to_f32(w.v_new[cu[r]:cu[r] + E]).astype(np.float64)
+        run = vp.sum(axis=0)[None] + np.cumsum(vn, axis=0)                   # sums over keys 0 .. P+i
+        mean = run / (P + 1 + np.arange(E))[:, None, None]                   # [E, Hkv, D]
+        want = np.repeat(mean, G, axis=1)                                    # q head h uses KV head h // G
+        err = np.abs(got[cu[r]:cu[r] + E] - want)
+        worst = max(worst, float(err.max()))
+        # the means are ~N(0, 1/n): bf16 rounding of the output dominates the error
+        assert err.max() <= 2.0 ** -8 * np.abs(want).max() + 1e-6, (r, err.max())
+    print("running mean: worst abs error", worst)
+    w.q[:] = q_saved
+    w.v_new[:] = 0x3F80
+    w.kv_pages[:, 1] = 0x3F80
+    ones = bf16_bits_to_f32(H.gpu_attention(w))
+    assert (ones == 1.0).all()
