@@ -62,3 +62,29 @@ def test_a_shape_beyond_the_scratch_size_is_refused_and_nothing_runs():
                                         c.extend_lens, c.out, torch.cuda.current_stream(), c.shape, check=False)
     assert st == cp.CP_ERR_WORKSPACE
     assert (c.out_bits() == 0x1234).all()
+
+
+def test_the_call_can_be_recorded_into_a_hip_graph_and_replayed():
+    """What the entry point is for: under stream capture nothing may allocate.  The call is made
+    once eagerly (the scratch address of the device is looked up then), recorded into a graph and
+    replayed three times with eager work in between; every replay must reproduce the eager bits."""
+    w = W.make_uniform("noalloc_graph", 781, 4, 8, 2, [900, 0, 2500, 64], [1, 3, 2, 1])    # decode-shaped: partials + merge
+    c = DeviceCase(w)
+    assert c.ws_bytes > 0
+    s = torch.cuda.current_stream()
+    call = lambda stream: cp.cp_extend_attention_noalloc(c.q, c.k_new, c.v_new, c.kv_pages, c.block_table,
+                                                         c.prefix_lens, c.extend_lens, c.out, stream, c.shape)
+    call(s)
+    want = c.out_bits().copy()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(torch.cuda.current_stream())
+    other = DeviceCase(W.make_uniform("noalloc_other", 782, 2, 8, 2, [300, 40], [200, 90]), 3)
+    for _ in range(3):
+        c.out.fill_(0x7FC1)
+        other.attention()                       # eager work that uses the same scratch in between
+        cp.cp_extend_attention_noalloc(other.q, other.k_new, other.v_new, other.kv_pages, other.block_table,
+                                       other.prefix_lens, other.extend_lens, other.out, s, other.shape)
+        torch.cuda.synchronize()
+        graph.replay()
+        assert (c.out_bits() == want).all()
