@@ -113,23 +113,19 @@ __device__ __forceinline__ int wave_inclusive_scan(int x, int lane)
     return x;
 }
 
-// K/V tile of 64 keys: each of the 512 threads stages two 16-byte chunks of K and two of V in
-// registers between the global load and the LDS store.
-struct TileRegs {
-    u32x4 k[2];
-    u32x4 v[2];
-};
-
 // LDS: four K buffers and four V buffers of one 64-key tile (16 KiB) each, tile t in buffer
-// t % 4.  A tile is written two iterations before its first use and V(t) is still read one
+// t % 4.  A tile is requested two iterations before its first use and V(t) is still read one
 // iteration after K(t); with one barrier per iteration that needs four buffers of each.
-// Rows are padded instead of swizzled so that every LDS read address is a per-lane base plus
-// an immediate: K rows have a pitch of 272 bytes (16 consecutive rows at the same column fall
-// into 16 different 16-byte bank groups), V rows a pitch of 320 bytes (the four consecutive
-// rows of a transposing read fall into four different 64-byte bank groups).
+// The tiles come from global memory straight into LDS (global_load_lds_dwordx4: lane i of a
+// wavefront writes 16 bytes at slot i of 1 KiB, no way through registers and no LDS store
+// instruction), so rows cannot be padded: they are 256 bytes apart and the 16-byte chunks
+// inside a row are swizzled instead.  K: chunk c of row r sits at slot c ^ (r & 15) (16
+// consecutive rows at the same column fall into 16 different 16-byte bank groups); V: at slot
+// c ^ ((r & 3) << 2) (the four consecutive rows of a transposing read fall into four different
+// 64-byte bank groups).
 constexpr int kNumBufs = 4;
-constexpr int kPitchK = 272;
-constexpr int kPitchV = 320;
+constexpr int kPitchK = 256;
+constexpr int kPitchV = 256;
 constexpr int kTileBytesK = kBN * kPitchK;
 constexpr int kTileBytesV = kBN * kPitchV;
 constexpr int kLdsBytes = kNumBufs * (kTileBytesK + kTileBytesV);
@@ -138,8 +134,8 @@ template <bool kSplit>
 __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams p)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    char *const lds_k = lds;                          // [4][64 rows][272 B]
-    char *const lds_v = lds + kNumBufs * kTileBytesK; // [4][64 rows][320 B]
+    char *const lds_k = lds;                          // [4][64 rows][256 B]
+    char *const lds_v = lds + kNumBufs * kTileBytesK; // [4][64 rows][256 B]
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -224,12 +220,20 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     }
 
     // ---- Q fragments, B operand of S^T = K Q^T: lane (j, h) holds q[row j][16 kk + 8 h ..+8)
+    // The fragments hold q * softmax_scale * log2(e), rounded to bf16 (nearest even) once per
+    // row: the accumulators of S^T are then the arguments of exp2 as they stand, which saves one
+    // multiply-add per score (a third of the softmax instructions).  The rounding moves every
+    // query element by at most half a bf16 unit in the last place.
+    const float c = p.scale_log2;
     bf16x8 qf[8];
     {
         const uint16_t *qp = p.q + (out_row * p.Hq + head) * kD + 8 * h;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk)
-            qf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qp + 16 * kk));
+        for (int kk = 0; kk < 8; ++kk) {
+            const bf16x8 raw = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qp + 16 * kk));
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qf[kk][e] = (__bf16)((float)raw[e] * c);
+        }
     }
 
     // ---- this thread's share of a K/V tile: key rows ld_row and ld_row + kLoadRows, 16-byte chunk
@@ -239,7 +243,10 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     const int ld_sub = lane >> 4;         // row within the wavefront's group of four
     const int ld_row = wave * 4 + ld_sub; // 0..kLoadRows-1
     const int ld_chunk = lane & 15;
-    const int32_t *table = p.block_table + (int64_t)r * p.max_pages;
+    // read-only for the whole launch and every index is wavefront-uniform: the constant address
+    // space keeps these loads on the scalar unit although the direct loads below write memory
+    const __attribute__((address_space(4))) int32_t *table =
+        (const __attribute__((address_space(4))) int32_t *)(p.block_table + (int64_t)r * p.max_pages);
     const int64_t v_plane = (int64_t)p.Hkv * kPS * kD; // K slab -> V slab inside a page
     const int64_t row_pitch = (int64_t)p.Hkv * kD;     // elements between rows of k_new
 
@@ -247,32 +254,63 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     // load step of the suffix, plus a per-lane byte offset that never changes.
     typedef const __attribute__((address_space(1))) char *gptr;
     const uint32_t row_bytes = (uint32_t)row_pitch * 2u;
-    const uint32_t pg_lane_k = (uint32_t)(((ld_row & 15) * kD + ld_chunk * 8) * 2); // inside a page's K slab
-    const uint32_t pg_lane_v = pg_lane_k + (uint32_t)(v_plane * 2);                  // same row, V slab
-    const uint32_t sfx_lane = (uint32_t)ld_row * row_bytes + (uint32_t)ld_chunk * 16u;
+    // Direct loads put lane i's 16 bytes into slot i of the wavefront's 1 KiB of LDS (4 rows of
+    // 16 slots), so the swizzle is applied on the source side: slot s of row r holds chunk
+    // s ^ (r & 15) of a K row and chunk s ^ ((r & 3) << 2) of a V row.
+    const int ck = ld_chunk ^ (ld_row & 15);
+    const int cv = ld_chunk ^ ((ld_row & 3) << 2);
+    const uint32_t pg_lane_k = (uint32_t)(((ld_row & 15) * kD + ck * 8) * 2); // inside a page's K slab
+    const uint32_t pg_lane_v = (uint32_t)(((ld_row & 15) * kD + cv * 8) * 2) + (uint32_t)(v_plane * 2);
+    const uint32_t sfx_lane_k = (uint32_t)ld_row * row_bytes + (uint32_t)ck * 16u;
+    const uint32_t sfx_lane_v = (uint32_t)ld_row * row_bytes + (uint32_t)cv * 16u;
+    // Four direct loads of 16 bytes per lane: K and V rows ld_row and ld_row + 32 of buffer buf.
+    // M0 carries the LDS address of the wavefront's 1 KiB.  The loads are written as assembly
+    // because the compiler, for the builtin, waits for every direct load in flight before the
+    // next LDS read of the wavefront, whichever buffer that read goes to; here the only reader
+    // of the loaded buffer is two barriers away, and dma_wait() in front of each barrier is the
+    // wait that is needed.  The compiler's own counts stay conservative: it does not see these
+    // loads, loads complete in order, so its waits can only cover more than it meant.
+    const uint32_t lds_k_wave = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds_k + wave * (4 * kPitchK);
+    const uint32_t lds_v_wave = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds_v + wave * (4 * kPitchV);
+    auto dma_tile = [&](gptr k0, gptr v0, gptr k1, gptr v1, int buf) {
+        const uint32_t dk0 = __builtin_amdgcn_readfirstlane(lds_k_wave + buf * kTileBytesK);
+        const uint32_t dv0 = __builtin_amdgcn_readfirstlane(lds_v_wave + buf * kTileBytesV);
+        const uint32_t dk1 = dk0 + kLoadRows * kPitchK, dv1 = dv0 + kLoadRows * kPitchV;
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm" // m0 is reserved; naming it documents the overwrite
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %4, off\n\t"
+                     "s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %5, off\n\t"
+                     "s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %6, off\n\t"
+                     "s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %7, off"
+                     :
+                     : "s"(dk0), "s"(dv0), "s"(dk1), "s"(dv1), "v"(k0), "v"(v0), "v"(k1), "v"(v1)
+                     : "memory", "m0");
+#pragma clang diagnostic pop
+    };
+    // all of this wavefront's direct loads have landed (the barrier that follows publishes them)
+    auto dma_wait = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
     const uint64_t page_bytes = (uint64_t)p.Hkv * (2u * kPS * kD * 2u);
     const gptr pages_head = (gptr)p.kv_pages + (int64_t)kvh * (kPS * kD * 2);
     const gptr knew_head = (gptr)p.k_new + ((int64_t)cu * p.Hkv + kvh) * (kD * 2);
     const gptr vnew_head = (gptr)p.v_new + ((int64_t)cu * p.Hkv + kvh) * (kD * 2);
-    auto load_tile = [&](int kt, TileRegs &tr) {
+    auto load_tile = [&](int kt, int buf) {
         if (kt < np_tiles && (kt + 1) * kBN <= P) {
+            gptr kp[2], vp[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const uint32_t page = (uint32_t)table[kt * (kBN / kPS) + 2 * i + (wave >> 2)];
                 const gptr base = pages_head + (uint64_t)page * page_bytes;
-                tr.k[i] = *(const __attribute__((address_space(1))) u32x4 *)(base + pg_lane_k);
-                tr.v[i] = *(const __attribute__((address_space(1))) u32x4 *)(base + pg_lane_v);
+                kp[i] = base + pg_lane_k;
+                vp[i] = base + pg_lane_v;
             }
+            dma_tile(kp[0], vp[0], kp[1], vp[1], buf);
             return;
         }
         if (kt >= np_tiles && (kt - np_tiles + 1) * kBN <= E) {
             const int64_t tile_off = (int64_t)(kt - np_tiles) * kBN * row_bytes;
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int64_t off = tile_off + (int64_t)(i * kLoadRows) * row_bytes;
-                tr.k[i] = *(const __attribute__((address_space(1))) u32x4 *)(knew_head + off + sfx_lane);
-                tr.v[i] = *(const __attribute__((address_space(1))) u32x4 *)(vnew_head + off + sfx_lane);
-            }
+            const int64_t off1 = tile_off + (int64_t)kLoadRows * row_bytes;
+            dma_tile(knew_head + tile_off + sfx_lane_k, vnew_head + tile_off + sfx_lane_v,
+                     knew_head + off1 + sfx_lane_k, vnew_head + off1 + sfx_lane_v, buf);
             return;
         }
         const uint16_t *ks[2];
@@ -284,8 +322,8 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
                 const int sub = min(ld_sub, P - 1 - tok0);
                 const int64_t page = table[tok0 >> 4];
                 const uint16_t *base = p.kv_pages + (page * 2 * p.Hkv + kvh) * (kPS * kD);
-                ks[i] = base + ((((tok0 + sub) & 15) * kD) + ld_chunk * 8);
-                vs[i] = ks[i] + v_plane;
+                ks[i] = base + ((((tok0 + sub) & 15) * kD) + ck * 8);
+                vs[i] = base + ((((tok0 + sub) & 15) * kD) + cv * 8) + v_plane;
             }
         } else {
 #pragma unroll
@@ -293,34 +331,28 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
                 const int srow0 = min((kt - np_tiles) * kBN + i * kLoadRows + wave * 4, E - 1);
                 const int sub = min(ld_sub, E - 1 - srow0);
                 const int64_t base = ((int64_t)(cu + srow0) * p.Hkv + kvh) * kD;
-                const int off = sub * (int)row_pitch + ld_chunk * 8;
-                ks[i] = p.k_new + base + off;
-                vs[i] = p.v_new + base + off;
+                const int off = sub * (int)row_pitch;
+                ks[i] = p.k_new + base + off + ck * 8;
+                vs[i] = p.v_new + base + off + cv * 8;
             }
         }
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            tr.k[i] = *(const __attribute__((address_space(1))) u32x4 *)(ks[i]);
-            tr.v[i] = *(const __attribute__((address_space(1))) u32x4 *)(vs[i]);
-        }
-    };
-    const int st_k = ld_row * kPitchK + ld_chunk * 16;
-    const int st_v = ld_row * kPitchV + ld_chunk * 16;
-    auto store_tile = [&](const TileRegs &tr, int buf) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            *reinterpret_cast<u32x4 *>(lds_k + buf * kTileBytesK + st_k + i * kLoadRows * kPitchK) = tr.k[i];
-            *reinterpret_cast<u32x4 *>(lds_v + buf * kTileBytesV + st_v + i * kLoadRows * kPitchV) = tr.v[i];
-        }
+        dma_tile((gptr)ks[0], (gptr)vs[0], (gptr)ks[1], (gptr)vs[1], buf);
     };
 
     // ---- per-lane LDS read offsets (bytes inside a tile buffer)
-    // K, A operand of S^T: lane (j, h) reads 16 bytes of key row kb*32 + j at chunk 2 kk + h.
-    const int k_lane = j * kPitchK + h * 16;
+    // K, A operand of S^T: lane (j, h) reads 16 bytes of key row kb*32 + j at chunk 2 kk + h,
+    // which the swizzle puts at slot (2 kk + h) ^ (j & 15): one offset per kk.
+    int k_lane[8];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) k_lane[kk] = j * kPitchK + (((2 * kk + h) ^ (j & 15)) << 4);
     // V^T, A operand of O^T = V^T P^T, through the transposing read: within a group of 16
     // lanes, lane i supplies the address of 4 consecutive d of key row k0 + i / 4 and receives
-    // V[k0 .. k0+3][d0 + i].  Here k0 = 4 h (+ 8 for the second read), d0 = 32 db + 16 (lane/16 % 2).
-    const int v_lane = (4 * h + ((lane & 15) >> 2)) * kPitchV + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
+    // V[k0 .. k0+3][d0 + i].  Here k0 = 4 h (+ 8 for the second read), d0 = 32 db + 16 (lane/16 % 2);
+    // the swizzle exchanges the 64-byte column blocks: block db of row r sits at db ^ (r & 3).
+    int v_lane[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+        v_lane[db] = (4 * h + ((lane & 15) >> 2)) * kPitchV + ((db ^ ((lane >> 2) & 3)) << 6) + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
 
     f32x16 o[4];
 #pragma unroll
@@ -329,7 +361,6 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
         for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
     float m_ref = -INFINITY; // reference maximum of the exponentials, log2 domain
     float l_run = 0.f;       // running sum over this half-wave's keys only
-    const float c = p.scale_log2;
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
     typedef f32x16 STile[kNKB];     // scores: 32-key blocks x 32 query rows
@@ -337,7 +368,7 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
 
     // S^T = K Q^T for the tile in K buffer kbuf.
     auto qk_tile = [&](int kbuf, STile &s) {
-        const char *kb = lds_k + kbuf * kTileBytesK + k_lane;
+        const char *kb = lds_k + kbuf * kTileBytesK;
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int b = 0; b < kNKB; ++b) s[b] = zero;
@@ -345,7 +376,7 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
         for (int kk = 0; kk < 8; ++kk) {
 #pragma unroll
             for (int b = 0; b < kNKB; ++b) {
-                const u32x4 a = *reinterpret_cast<const u32x4 *>(kb + kk * 32 + b * 32 * kPitchK);
+                const u32x4 a = *reinterpret_cast<const u32x4 *>(kb + k_lane[kk] + b * 32 * kPitchK);
                 s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), qf[kk], s[b], 0, 0, 0);
             }
         }
@@ -362,13 +393,13 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
         __builtin_amdgcn_sched_group_barrier(0x008, kFragsAhead, 0);
     };
     // O^T += V^T P^T for the tile in V buffer vbuf: 4 d blocks x steps of 16 keys.
-    auto pv_tile = [&](int vbuf, const PTile &pb, auto with_store) {
-        const char *vb = lds_v + vbuf * kTileBytesV + v_lane;
+    auto pv_tile = [&](int vbuf, const PTile &pb) {
+        const char *vb = lds_v + vbuf * kTileBytesV;
 #pragma unroll
         for (int ks = 0; ks < 2 * kNKB; ++ks) { // keys ks*16 .. ks*16+15
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
-                const char *a = vb + db * 64 + ks * 16 * kPitchV;
+                const char *a = vb + v_lane[db] + ks * 16 * kPitchV;
                 const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                     (__attribute__((address_space(3))) s16x4 *)(a));
                 const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -377,20 +408,17 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
                 o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pb[ks], o[db], 0, 0, 0);
             }
         }
-        // Same for the V fragments (two transposing reads each), four MFMAs ahead, with two of
-        // the next tile's 32 exponentials behind every MFMA where the caller has them in the
-        // same block (the other VALU work follows its exponentials by dependency).
+        // Same for the V fragments (two transposing reads each), four MFMAs ahead, with up to
+        // four VALU instructions of the next tile's softmax (64 in all: 32 exponentials, 16
+        // conversions, 16 row-sum steps) behind every MFMA where the caller has them in the same
+        // block.
         constexpr int kFragsAhead = 4;
-        constexpr bool kStore = decltype(with_store)::value;
         __builtin_amdgcn_sched_group_barrier(0x100, 2 * kFragsAhead, 0);
 #pragma unroll
         for (int i = 0; i < 8 * kNKB; ++i) {
-            // the caller's four LDS writes of the next tile go between the last MFMAs, where
-            // their latency is covered, instead of in front of the barrier
-            if (kStore && i == 8 * kNKB - 2) __builtin_amdgcn_sched_group_barrier(0x200, 4, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             if (i < 8 * kNKB - kFragsAhead) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 4, 0);
         }
     };
     // Masks the keys of a boundary tile that the lane's row must not see.  Accumulator element
@@ -405,16 +433,19 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     };
     // Exponentials of one tile against the reference m_use (log2 domain), one query row per
     // lane: bf16 probabilities in B-operand order (pb[2b + u] element e is accumulator element
-    // 8u + e of block b); returns their sum over this lane's keys.
-    auto exp_tile = [&](const STile &s, PTile &pb, float m_use) -> float {
+    // 8u + e of block b); returns their sum over this lane's keys.  `plain` says that the
+    // reference is 0 for every row of the wavefront: then there is nothing to subtract.
+    auto exp_tile = [&](const STile &s, PTile &pb, float m_use, auto plain) -> float {
+        constexpr bool kPlain = decltype(plain)::value;
         float psum = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; e += 2)
 #pragma unroll
             for (int t = 0; t < 2 * kNKB; ++t) {
                 f32x2 x;
-                x[0] = fast_exp2(fmaf(s[t >> 1][8 * (t & 1) + e], c, -m_use));
-                x[1] = fast_exp2(fmaf(s[t >> 1][8 * (t & 1) + e + 1], c, -m_use));
+                const float s0 = s[t >> 1][8 * (t & 1) + e], s1 = s[t >> 1][8 * (t & 1) + e + 1];
+                x[0] = fast_exp2(kPlain ? s0 : s0 - m_use);
+                x[1] = fast_exp2(kPlain ? s1 : s1 - m_use);
                 const bf16x2 y = __builtin_convertvector(x, bf16x2);
                 psum = __builtin_amdgcn_fdot2_f32_bf16(y, ones, psum, false);
                 pb[t][e] = y[0];
@@ -440,35 +471,36 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     // ---- main loop, one barrier per key tile.  Iteration `it`:
     //     fetch tile it+2 from global memory into registers
     //     S = K(it) Q^T                                            (MFMA)
-    //     p = exp2(S c - m_ref) next to O += V(it-1)^T P(it-1)^T   (VALU next to MFMA)
+    //     p = exp2(S - m_ref) next to O += V(it-1)^T P(it-1)^T     (VALU next to MFMA)
     //     write tile it+2 to LDS buffer (it+2) % 4, barrier
-    // The exponentials are taken against the running reference m_ref WITHOUT first reducing
-    // the row maximum of the tile.  Only when some row of the wavefront has no reference yet,
-    // or its sum shows that the reference is stale by more than a factor 2^30, is the tile
-    // redone the classic way (row maximum, new reference, rescale of O and l); any reference
-    // gives the same result after the final division as long as nothing overflows, and fp32
-    // leaves ~2^97 of headroom above that trigger.
-    TileRegs tr;
-    load_tile(kt_begin, tr);
-    store_tile(tr, 0);
-    if (n_it > 1) {
-        load_tile(kt_begin + 1, tr);
-        store_tile(tr, 1);
-    }
+    // (S already carries softmax_scale * log2(e), see the Q fragments.)  The exponentials are
+    // taken against the running reference m_ref WITHOUT first reducing the row maximum of the
+    // tile.  Only when some row of the wavefront has no reference yet, or its sum shows that the
+    // reference is stale by a factor 2^80 or more, is the tile redone the classic way (row
+    // maximum, new reference, rescale of O and l).  Any reference gives the same result after
+    // the final division as long as nothing overflows or vanishes: a row maximum inside
+    // [-kSnap, kSnap] takes the reference 0 (exponentials between 2^-64 and 2^64 at the top of
+    // the row, nothing to subtract), and below the trigger the sums stay under 2^80 times the
+    // number of keys, which fp32 holds up to 2^47 keys of magnitude 1.
+    load_tile(kt_begin, 0);
+    if (n_it > 1) load_tile(kt_begin + 1, 1);
+    dma_wait();
     __syncthreads();
 
     bool have_prev = false; // the previous tile's probabilities still wait for their P V
-    constexpr float kStale = 1073741824.f; // 2^30
+    constexpr float kStale = 1.2089258196146292e24f; // 2^80
+    constexpr float kSnap = 64.f; // a row whose maximum lies in [-64, 64] takes the reference 0
 
     // Classic online-softmax step: row maximum, new reference, rescale of O and l.
     auto redo_tile = [&](const STile &s, PTile &pb) -> float {
-        const float m_new = fmaxf(m_ref, row_max(s) * c);
+        float m_new = fmaxf(m_ref, row_max(s));
+        if (fabsf(m_new) <= kSnap) m_new = 0.f;
         const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = fast_exp2(m_ref - m_use);
         rescale_o(alpha);
         l_run *= alpha;
         m_ref = m_new;
-        return exp_tile(s, pb, m_use);
+        return exp_tile(s, pb, m_use, std::false_type{});
     };
     // first key of tile kt in its own numbering (prefix tokens or suffix rows)
     auto tile_key0 = [&](int kt) { return kt >= np_tiles ? (kt - np_tiles) * kBN : kt * kBN; };
@@ -490,14 +522,14 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     // iteration 0: no previous tile yet, and no reference: classic step
     {
         const bool prefetch = 2 < n_it;
-        if (prefetch) load_tile(kt_begin + 2, tr);
+        if (prefetch) load_tile(kt_begin + 2, 2);
         if (!skipped(kt_begin)) {
             STile s;
             masked_qk(kt_begin, 0, s);
             l_run += redo_tile(s, pb_a);
             have_prev = true;
         }
-        if (prefetch) store_tile(tr, 2);
+        dma_wait();
         __syncthreads();
     }
     // One full step; only called for tiles this wavefront does not skip (so the previous tile
@@ -506,16 +538,16 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
         const int buf = it & 3;
         const int kt = kt_begin + it;
         const bool prefetch = it + 2 < n_it;
-        if (prefetch) load_tile(kt + 2, tr);
+        if (prefetch) load_tile(kt + 2, (buf + 2) & 3);
         STile s;
         masked_qk(kt, buf, s);
         // one basic block: the exponentials (VALU) interleave with P V (MFMA)
-        float psum = exp_tile(s, pb_cur, (m_ref == -INFINITY) ? 0.f : m_ref);
-        pv_tile((buf + 3) & 3, pb_prev, std::false_type{});
+        float psum = exp_tile(s, pb_cur, (m_ref == -INFINITY) ? 0.f : m_ref, std::false_type{});
+        pv_tile((buf + 3) & 3, pb_prev);
         if (__builtin_amdgcn_ballot_w64(!(psum < kStale) || m_ref == -INFINITY) != 0)
             psum = redo_tile(s, pb_cur);
         l_run += psum;
-        if (prefetch) store_tile(tr, (buf + 2) & 3);
+        dma_wait();
         __syncthreads();
     };
     int it = 1;
@@ -541,7 +573,9 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
                 return (uint32_t)table[min(kt * (kBN / kPS) + 2 * i + tsel, last_entry)];
             };
             uint32_t pg0 = entry(kt_begin + it + 2, 0), pg1 = entry(kt_begin + it + 2, 1);
-            for (; it < fast_end; ++it) {
+            // while every row of the wavefront has the reference 0 (the usual case, see kSnap);
+            // otherwise the general step below takes over
+            for (; it < fast_end && __builtin_amdgcn_ballot_w64(m_ref != 0.f) == 0; ++it) {
                 const int buf = it & 3;
                 const int kt2 = kt_begin + it + 2;
                 gptr k0, v0, k1, v1;
@@ -553,27 +587,23 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
                     k1 = b1 + pg_lane_k;
                     v1 = b1 + pg_lane_v;
                 } else {
-                    const int64_t off = (int64_t)(kt2 - np_tiles) * kBN * row_bytes + sfx_lane;
-                    k0 = knew_head + off;
-                    v0 = vnew_head + off;
+                    const int64_t off = (int64_t)(kt2 - np_tiles) * kBN * row_bytes;
+                    k0 = knew_head + off + sfx_lane_k;
+                    v0 = vnew_head + off + sfx_lane_v;
                     k1 = k0 + (int64_t)kLoadRows * row_bytes;
                     v1 = v0 + (int64_t)kLoadRows * row_bytes;
                 }
-                tr.k[0] = *(const __attribute__((address_space(1))) u32x4 *)k0;
-                tr.v[0] = *(const __attribute__((address_space(1))) u32x4 *)v0;
-                tr.k[1] = *(const __attribute__((address_space(1))) u32x4 *)k1;
-                tr.v[1] = *(const __attribute__((address_space(1))) u32x4 *)v1;
+                dma_tile(k0, v0, k1, v1, (buf + 2) & 3);
                 pg0 = entry(kt_begin + it + 3, 0);
                 pg1 = entry(kt_begin + it + 3, 1);
-                __builtin_amdgcn_sched_group_barrier(0x020, 4, 0); // the tile loads go first
                 STile s;
                 qk_tile(buf, s);
-                float psum = exp_tile(s, pb_b, (m_ref == -INFINITY) ? 0.f : m_ref);
-                pv_tile((buf + 3) & 3, pb_a, std::true_type{});
-                store_tile(tr, (buf + 2) & 3);
+                float psum = exp_tile(s, pb_b, 0.f, std::true_type{});
+                pv_tile((buf + 3) & 3, pb_a);
                 if (__builtin_amdgcn_ballot_w64(!(psum < kStale) || m_ref == -INFINITY) != 0)
                     psum = redo_tile(s, pb_b);
                 l_run += psum;
+                dma_wait();
                 __syncthreads();
 #pragma unroll
                 for (int t = 0; t < 2 * kNKB; ++t) pb_a[t] = pb_b[t];
@@ -586,15 +616,15 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
             for (int t = 0; t < 2 * kNKB; ++t) pb_a[t] = pb_b[t];
         }
         // P V of the last tile this wavefront computed (tile it - 1)
-        pv_tile((it - 1) & 3, pb_a, std::false_type{});
+        pv_tile((it - 1) & 3, pb_a);
     }
     // remaining tiles are invisible to this wavefront: only take part in the cooperative loads
     for (; it < n_it; ++it) {
         const bool prefetch = it + 2 < n_it;
         if (prefetch) {
-            load_tile(kt_begin + it + 2, tr);
-            store_tile(tr, (it + 2) & 3);
+            load_tile(kt_begin + it + 2, (it + 2) & 3);
         }
+        dma_wait();
         __syncthreads();
     }
 

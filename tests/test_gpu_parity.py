@@ -190,6 +190,51 @@ def test_value_ones_and_key_shift(H):
     _check(H.gpu_attention(w), oracle.attention_of(w), "key shift")
 
 
+def _with_score_offsets(name, seed, P, E, offsets_of_key):
+    """One request whose key j scores about offsets_of_key[j] (natural units, before the
+    softmax) against every query row, on top of the N(0,1) noise of the other dimensions: the
+    first four dimensions of every query are 8 and those of key j are offsets[j] / (32 scale)."""
+    w = W.make_uniform(name, seed, 1, 4, 2, P, E)
+    off = np.asarray(offsets_of_key, dtype=np.float32)
+    assert off.shape == (P + E,)
+    kval = off / np.float32(32.0 * w.softmax_scale)
+    qf = bf16_bits_to_f32(w.q); qf[..., :4] = 8.0; w.q = f32_to_bf16_bits(qf)
+    kf = bf16_bits_to_f32(w.k_new); kf[..., :4] = kval[P:, None, None]; w.k_new = f32_to_bf16_bits(kf)
+    pf = bf16_bits_to_f32(w.kv_pages[:, 0])              # [page][head][slot][d]
+    for j in range(P):
+        pf[w.block_table[0, j // 16], :, j % 16, :4] = kval[j]
+    w.kv_pages[:, 0] = f32_to_bf16_bits(pf)
+    return w
+
+
+# Score levels along the key sequence (natural units; times 1.44 in the exp2 domain of the
+# kernel).  The row-tiled kernel keeps the reference exponent 0 while a row's maximum stays
+# within 2^+-64, takes the row maximum as reference beyond that, and redoes a tile when a later
+# key beats the reference by 2^80: every schedule below walks a different path through that.
+_SCORE_SCHEDULES = {
+    "mild": [-5, 5, 0, 8, -8, 3],
+    "wide_but_plain": [-40, 40, -40, 0, 40, -20],
+    "climb": [-120, -80, -50, 10, 90, 150],
+    "descend": [150, 90, 10, -50, -80, -120],
+    "all_very_negative": [-100, -101, -99, -100, -102, -100],
+    "from_very_negative_into_the_plain_range": [-100, -100, -30, -30, 0, 0],
+    "late_spike_beyond_the_plain_range": [0, 0, 0, 0, 60, 0],
+    "swing_inside_the_plain_range": [-30, -30, -30, -30, 30, -30],
+    "stale_reference_below_the_trigger": [-100, -100, -60, -60, -50, -100],
+}
+
+
+@pytest.mark.parametrize("splits", [1, 3])
+@pytest.mark.parametrize("schedule", sorted(_SCORE_SCHEDULES))
+def test_score_ranges_and_reference_changes(H, schedule, splits):
+    P, E = 328, 200                                       # 9 key tiles, ragged on both sides
+    levels = _SCORE_SCHEDULES[schedule]
+    seg = -(-(P + E) // len(levels))
+    off = np.repeat(np.asarray(levels, dtype=np.float32), seg)[:P + E]
+    w = _with_score_offsets(f"scores_{schedule}", 130 + len(schedule), P, E, off)
+    _check(H.gpu_attention(w, num_splits=splits), oracle.attention_of(w), f"{schedule} splits={splits}")
+
+
 def test_error_paths_return_codes(H):
     import paper_2511_03475_amd as cp
     w = W.make_uniform("err", 110, 1, 4, 2, 32, 32)
