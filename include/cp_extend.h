@@ -109,7 +109,12 @@ int32_t cp_plan_kind(const cp_shape *shape);
  *     s_j = softmax_scale * <q[cu[r]+i, h, :], key(j)>       for j = 0 .. P_r + i
  *     out[cu[r]+i, h, :] = sum_j softmax(s)_j * val(j)
  * Products are bf16 x bf16 accumulated in fp32, the softmax is fp32, out is rounded to bf16
- * (nearest even).  The suffix K/V is read from k_new / v_new, never from kv_pages, so the
+ * (nearest even).  The row-tiled kernel first multiplies each query element by
+ * softmax_scale * log2(e) and rounds it to bf16 (nearest even), so that the products are the
+ * exponents of 2 directly: the result is the attention of a query that differs from the given
+ * one by at most half a bf16 unit in the last place per element, i.e. by no more than the
+ * rounding the query already carries; the decode-shaped kernel scales the fp32 scores instead.
+ * The suffix K/V is read from k_new / v_new, never from kv_pages, so the
  * result does not depend on whether cp_write_kv ran before, after or not at all.  kv_pages is
  * only read.  Results are bitwise reproducible for a fixed shape (no atomics).
  *

@@ -8,11 +8,12 @@
  * power limit, so constant operands run at the published rate and random ones do not.
  *
  * cp_probe_mix adds what the attention kernel does per MFMA besides the product: the A operand
- * is read from LDS (16 bytes per lane) and, for every second MFMA, two values go through fma +
- * exp2, one packed conversion to bf16 and one dot2 row-sum step (per MFMA: 1 exp2, 1 fma, 1/2
- * cvt, 1/2 dot2 - the attention kernel's softmax per score).  No global loads, LDS writes,
- * barriers or waits for fresh MFMA results: it is the ceiling of that instruction mix on this
- * device, in instruction issue and in power.
+ * is read from LDS (16 bytes per lane) and, for every second MFMA, two values go through exp2,
+ * one packed conversion to bf16 and one dot2 row-sum step (per MFMA: 1 exp2, 1/2 cvt, 1/2 dot2
+ * - the attention kernel's softmax per score).  No global loads, barriers or waits for fresh
+ * MFMA results: it is the ceiling of that instruction mix on this device, in instruction issue
+ * and in power.  In both probes the accumulators return to zero every eight trips (the B
+ * operands come in pairs of opposite sign), so the values stay in a realistic range.
  */
 #ifndef CP_PROBE_H
 #define CP_PROBE_H

@@ -14,7 +14,10 @@
 // (lane % 32) is a query row: the softmax row reductions are then in-lane plus one exchange
 // between the two half-waves, the bf16 probabilities already sit in the B-operand layout of the
 // second product O^T = V^T P^T, and the per-row rescale of O is a per-lane scalar multiply.
-// V^T fragments come from LDS through the transposing read ds_read_b64_tr_b16.
+// V^T fragments come from LDS through the transposing read ds_read_b64_tr_b16.  The K/V tiles
+// reach LDS by direct loads (global_load_lds_dwordx4), without a pass through registers.  The
+// query fragments carry softmax_scale * log2(e), rounded to bf16 once per row, so that the
+// accumulators of S^T are the arguments of exp2 as they stand.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -276,16 +279,13 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
         const uint32_t dk0 = __builtin_amdgcn_readfirstlane(lds_k_wave + buf * kTileBytesK);
         const uint32_t dv0 = __builtin_amdgcn_readfirstlane(lds_v_wave + buf * kTileBytesV);
         const uint32_t dk1 = dk0 + kLoadRows * kPitchK, dv1 = dv0 + kLoadRows * kPitchV;
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm" // m0 is reserved; naming it documents the overwrite
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %4, off\n\t"
                      "s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %5, off\n\t"
                      "s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %6, off\n\t"
                      "s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %7, off"
                      :
                      : "s"(dk0), "s"(dv0), "s"(dk1), "s"(dv1), "v"(k0), "v"(v0), "v"(k1), "v"(v1)
-                     : "memory", "m0");
-#pragma clang diagnostic pop
+                     : "memory"); // m0 is reserved: the compiler keeps nothing in it across statements
     };
     // all of this wavefront's direct loads have landed (the barrier that follows publishes them)
     auto dma_wait = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
@@ -408,11 +408,11 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
                 o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pb[ks], o[db], 0, 0, 0);
             }
         }
-        // Same for the V fragments (two transposing reads each), four MFMAs ahead, with up to
+        // Same for the V fragments (two transposing reads each), five MFMAs ahead, with up to
         // four VALU instructions of the next tile's softmax (64 in all: 32 exponentials, 16
         // conversions, 16 row-sum steps) behind every MFMA where the caller has them in the same
         // block.
-        constexpr int kFragsAhead = 4;
+        constexpr int kFragsAhead = 5;
         __builtin_amdgcn_sched_group_barrier(0x100, 2 * kFragsAhead, 0);
 #pragma unroll
         for (int i = 0; i < 8 * kNKB; ++i) {
@@ -786,7 +786,10 @@ __global__ __launch_bounds__(256) void merge_few_splits_kernel(const float *__re
 constexpr int kDecRows = 32;            // (head, token) rows per wavefront
 constexpr int kDecMaxRowBlocks = 2;     // row blocks per (request, KV head): G x E_r <= 64 (beyond, the row-tiled kernel is faster)
 constexpr int kDecWaves = 4;            // wavefronts per workgroup (independent of each other)
-constexpr int kDecPitchK = 272;         // LDS bytes per K row / V row (256 + padding, as above)
+// LDS bytes per K row / V row: 256 + padding.  16 consecutive K rows at the same column fall into
+// 16 different 16-byte bank groups, the four consecutive V rows of a transposing read into four
+// different 64-byte bank groups, and every read address is a per-lane base plus an immediate.
+constexpr int kDecPitchK = 272;
 constexpr int kDecPitchV = 320;
 constexpr int kDecLdsK = 32 * kDecPitchK;
 constexpr int kDecLdsPerWave = kDecLdsK + 32 * kDecPitchV;
