@@ -51,6 +51,15 @@ double cp_probe_mfma_flops(int32_t iters);
  */
 int cp_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/*
+ * Test aid: fills the whole LDS (160 KiB) of every compute unit with the 32-bit `pattern`
+ * (eight workgroups per compute unit, one after the other), so that the next kernel on the
+ * stream starts with known leftovers.  A kernel whose result depends on LDS it did not write
+ * itself shows up as a result that changes with the pattern (NaN patterns: 0x7FC07FC0,
+ * 0xFFFFFFFF).  Returns 0 or -4 (HIP error).
+ */
+int cp_probe_fill_lds(uint32_t pattern, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

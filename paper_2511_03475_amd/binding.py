@@ -26,7 +26,7 @@ CP_ERR_LENGTHS = -7
 
 EXPORTS = ("cp_workspace_bytes", "cp_num_splits", "cp_plan_kind", "cp_extend_attention", "cp_write_kv",
            "cp_extend_attention_noalloc", "cp_noalloc_scratch_bytes",
-           "cp_status_string", "cp_check_tables", "cp_set_debug_validate", "cp_context_distance", "cp_probe_mfma", "cp_probe_mix", "cp_probe_copy",
+           "cp_status_string", "cp_check_tables", "cp_set_debug_validate", "cp_context_distance", "cp_probe_mfma", "cp_probe_mix", "cp_probe_copy", "cp_probe_fill_lds",
            "cp_probe_mfma_sink_floats", "cp_probe_mfma_flops",
            "cp_index_distinct", "cp_index_build", "cp_index_free", "cp_index_num_contexts",
            "cp_index_num_nodes", "cp_index_aligned", "cp_index_path", "cp_index_leaf", "cp_index_node",
@@ -101,6 +101,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.cp_probe_mix.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.cp_probe_copy.restype = ctypes.c_int
     lib.cp_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    lib.cp_probe_fill_lds.restype = ctypes.c_int
+    lib.cp_probe_fill_lds.argtypes = [ctypes.c_uint32, vp]
     lib.cp_probe_mfma_sink_floats.restype = ctypes.c_size_t
     lib.cp_probe_mfma_sink_floats.argtypes = []
     lib.cp_probe_mfma_flops.restype = ctypes.c_double
@@ -276,6 +278,14 @@ def cp_probe_mix(operands: int, iters: int, sink, stream, check: bool = True) ->
     st = load_library().cp_probe_mix(int(operands), int(iters), _ptr(sink), _stream(stream))
     if check and st != CP_OK:
         raise CpError(st, "cp_probe_mix")
+    return st
+
+
+def cp_probe_fill_lds(pattern: int, stream, check: bool = True) -> int:
+    """Fills the LDS of every compute unit with a 32-bit pattern (test aid, see cp_probe.h)."""
+    st = load_library().cp_probe_fill_lds(int(pattern) & 0xFFFFFFFF, _stream(stream))
+    if check and st != 0:
+        raise CpError(st, "cp_probe_fill_lds")
     return st
 
 

@@ -3,6 +3,7 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <mutex>
 
 #include "cp_probe.h"
 
@@ -124,6 +125,19 @@ __global__ __launch_bounds__(256) void copy_kernel(u32x4 *__restrict__ dst, cons
     }
 }
 
+// Every thread writes its share of the 160 KiB and reads it back (so that the stores cannot be
+// dropped); the flag is never set for a pattern the caller can pass twice in one word.
+constexpr int kLdsFillBytes = 160 * 1024;
+__global__ __launch_bounds__(1024) void fill_lds_kernel(unsigned pattern, unsigned *flag)
+{
+    extern __shared__ unsigned fill_words[];
+    for (int i = threadIdx.x; i < kLdsFillBytes / 4; i += 1024) fill_words[i] = pattern;
+    __syncthreads();
+    unsigned x = 0;
+    for (int i = threadIdx.x; i < kLdsFillBytes / 4; i += 1024) x |= fill_words[i] ^ pattern;
+    if (x != 0 && flag) *flag = x;
+}
+
 int launch(bool with_mix, int32_t operands, int32_t iters, float *sink, void *stream)
 {
     if (!sink) return -1;
@@ -162,5 +176,19 @@ extern "C" int cp_probe_copy(void *dst, const void *src, size_t bytes, void *str
     const size_t per_block = 256 * kCopyUnroll;
     const unsigned blocks = (unsigned)std::min<size_t>((n + per_block - 1) / per_block, 256u * 16u);
     hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (u32x4 *)dst, (const u32x4 *)src, n);
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+extern "C" int cp_probe_fill_lds(uint32_t pattern, void *stream)
+{
+    static std::once_flag once;
+    static hipError_t attr = hipSuccess;
+    std::call_once(once, [] {
+        attr = hipFuncSetAttribute((const void *)fill_lds_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   kLdsFillBytes);
+    });
+    if (attr != hipSuccess) return -4;
+    hipLaunchKernelGGL(fill_lds_kernel, dim3(kBlocks * 8), dim3(1024), kLdsFillBytes, (hipStream_t)stream, pattern,
+                       (unsigned *)nullptr);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }

@@ -235,6 +235,33 @@ def test_score_ranges_and_reference_changes(H, schedule, splits):
     _check(H.gpu_attention(w, num_splits=splits), oracle.attention_of(w), f"{schedule} splits={splits}")
 
 
+@pytest.mark.parametrize("case", ["row_tiled_ragged", "row_tiled_split", "packed_heads", "decode"])
+def test_leftover_lds_contents_do_not_reach_the_result(H, case):
+    """The kernels read only LDS they wrote in the same launch: the output bits do not depend on
+    what an earlier kernel left in LDS, NaN and infinity patterns included."""
+    import torch
+    import paper_2511_03475_amd as cp
+    if case == "row_tiled_ragged":
+        w, ns = W.make_uniform("lds_a", 141, 3, 8, 2, [333, 0, 1000], [500, 700, 77]), 0
+    elif case == "row_tiled_split":
+        w, ns = W.make_uniform("lds_b", 142, 2, 4, 2, [2000, 900], [130, 300]), 3
+    elif case == "packed_heads":
+        w, ns = W.make_uniform("lds_c", 143, 4, 16, 2, [700, 300, 64, 1], [40, 100, 128, 9]), 1
+    else:
+        w, ns = W.make_uniform("lds_d", 144, 5, 16, 2, [3000, 1, 517, 64, 2048], [1, 2, 1, 4, 3]), 0
+    case_ = H.DeviceCase(w, ns)
+    stream = torch.cuda.current_stream()
+    outs = []
+    for pattern in (0x00000000, 0x7FC07FC0, 0xFFFFFFFF, 0x7F807F80, 0xFF80FF80, 0x3F803F80):
+        case_.out.fill_(0x5555)
+        cp.cp_probe_fill_lds(pattern, stream)
+        case_.attention()
+        outs.append(case_.out_bits().copy())
+    for o in outs[1:]:
+        assert np.array_equal(o, outs[0])
+    _check(outs[0], oracle.attention_of(w), f"lds leftovers {case}")
+
+
 def test_error_paths_return_codes(H):
     import paper_2511_03475_amd as cp
     w = W.make_uniform("err", 110, 1, 4, 2, 32, 32)
