@@ -469,10 +469,10 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     };
 
     // ---- main loop, one barrier per key tile.  Iteration `it`:
-    //     fetch tile it+2 from global memory into registers
+    //     request tile it+2: global memory -> LDS buffer (it+2) % 4, asynchronously
     //     S = K(it) Q^T                                            (MFMA)
     //     p = exp2(S - m_ref) next to O += V(it-1)^T P(it-1)^T     (VALU next to MFMA)
-    //     write tile it+2 to LDS buffer (it+2) % 4, barrier
+    //     wait for the requested tile, barrier
     // (S already carries softmax_scale * log2(e), see the Q fragments.)  The exponentials are
     // taken against the running reference m_ref WITHOUT first reducing the row maximum of the
     // tile.  Only when some row of the wavefront has no reference yet, or its sum shows that the
