@@ -422,3 +422,34 @@ def test_random_shapes_attention_and_cache_write(H, seed):
     np.testing.assert_array_equal(
         case.pool_bits(),
         oracle.write_kv(w.k_new, w.v_new, w.kv_pages, w.block_table, w.prefix_lens, w.extend_lens))
+
+
+def _wide_random_shape(rng):
+    """A wider draw than _random_shape: up to 70 requests, G up to 16, eight KV heads, long prefixes."""
+    B = int(rng.choice([1, 2, 3, 5, 9, 70]))
+    Hkv = int(rng.choice([1, 2, 3, 8]))
+    G = int(rng.choice([1, 2, 3, 4, 6, 8, 16]))
+    regime = rng.choice(["decode", "short", "mid", "long", "long_prefix"])
+    hiE = {"decode": 6, "short": 70, "mid": 300, "long": 700, "long_prefix": 150}[regime]
+    hiP = {"decode": 3000, "short": 900, "mid": 900, "long": 500, "long_prefix": 4000}[regime]
+    if B == 70:
+        hiE, hiP = min(hiE, 40), min(hiP, 300)
+    E = rng.integers(0, hiE, size=B)
+    P = rng.integers(0, hiP, size=B)
+    if E.sum() == 0:
+        E[0] = 1
+    snap = rng.random(B) < 0.5
+    P[snap] = (P[snap] // 64) * 64
+    return B, G, Hkv, [int(x) for x in P], [int(x) for x in E]
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_wide_random_shapes_attention(H, seed):
+    rng = np.random.default_rng(770000 + seed)
+    B, G, Hkv, P, E = _wide_random_shape(rng)
+    w = W.make_uniform("fuzz_wide", 770000 + seed, B, G * Hkv, Hkv, P, E)
+    want = oracle.attention_of(w)
+    what = f"seed={seed} B={B} G={G} Hkv={Hkv} P={P} E={E}"
+    _check(H.gpu_attention(w), want, what + " auto")
+    ns = int(rng.integers(1, 9))
+    _check(H.gpu_attention(w, num_splits=ns), want, what + f" splits={ns}")
