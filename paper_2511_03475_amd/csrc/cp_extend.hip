@@ -116,9 +116,13 @@ __device__ __forceinline__ int wave_inclusive_scan(int x, int lane)
     return x;
 }
 
-// LDS: four K buffers and four V buffers of one 64-key tile (16 KiB) each, tile t in buffer
-// t % 4.  A tile is requested two iterations before its first use and V(t) is still read one
-// iteration after K(t); with one barrier per iteration that needs four buffers of each.
+// LDS: four K buffers and five V buffers of one 64-key tile (16 KiB) each, K of tile t in buffer
+// t % 4, V in buffer t % 5.  A tile is requested two iterations before its first use and V(t) is
+// still read one iteration after K(t).  The workgroup meets at a barrier only after every second
+// tile (tiles 2m+1 and 2m+2 form an interval): within an interval K(2m+1), K(2m+2), V(2m) and
+// V(2m+1) are read, V(2m+2) is resident, and tiles 2m+3 and 2m+4 arrive, which takes four K
+// buffers and five V buffers if no arriving tile is to overwrite one that a slower wavefront of
+// the same interval still reads.
 // The tiles come from global memory straight into LDS (global_load_lds_dwordx4: lane i of a
 // wavefront writes 16 bytes at slot i of 1 KiB, no way through registers and no LDS store
 // instruction), so rows cannot be padded: they are 256 bytes apart and the 16-byte chunks
@@ -131,14 +135,15 @@ constexpr int kPitchK = 256;
 constexpr int kPitchV = 256;
 constexpr int kTileBytesK = kBN * kPitchK;
 constexpr int kTileBytesV = kBN * kPitchV;
-constexpr int kLdsBytes = kNumBufs * (kTileBytesK + kTileBytesV);
+constexpr int kNumBufsV = 5;
+constexpr int kLdsBytes = kNumBufs * kTileBytesK + kNumBufsV * kTileBytesV;
 
 template <bool kSplit>
 __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams p)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     char *const lds_k = lds;                          // [4][64 rows][256 B]
-    char *const lds_v = lds + kNumBufs * kTileBytesK; // [4][64 rows][256 B]
+    char *const lds_v = lds + kNumBufs * kTileBytesK; // [5][64 rows][256 B]
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -275,9 +280,9 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     // loads, loads complete in order, so its waits can only cover more than it meant.
     const uint32_t lds_k_wave = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds_k + wave * (4 * kPitchK);
     const uint32_t lds_v_wave = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds_v + wave * (4 * kPitchV);
-    auto dma_tile = [&](gptr k0, gptr v0, gptr k1, gptr v1, int buf) {
-        const uint32_t dk0 = __builtin_amdgcn_readfirstlane(lds_k_wave + buf * kTileBytesK);
-        const uint32_t dv0 = __builtin_amdgcn_readfirstlane(lds_v_wave + buf * kTileBytesV);
+    auto dma_tile = [&](gptr k0, gptr v0, gptr k1, gptr v1, int kbuf, int vbuf) {
+        const uint32_t dk0 = __builtin_amdgcn_readfirstlane(lds_k_wave + kbuf * kTileBytesK);
+        const uint32_t dv0 = __builtin_amdgcn_readfirstlane(lds_v_wave + vbuf * kTileBytesV);
         const uint32_t dk1 = dk0 + kLoadRows * kPitchK, dv1 = dv0 + kLoadRows * kPitchV;
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %4, off\n\t"
                      "s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %5, off\n\t"
@@ -293,7 +298,8 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
     const gptr pages_head = (gptr)p.kv_pages + (int64_t)kvh * (kPS * kD * 2);
     const gptr knew_head = (gptr)p.k_new + ((int64_t)cu * p.Hkv + kvh) * (kD * 2);
     const gptr vnew_head = (gptr)p.v_new + ((int64_t)cu * p.Hkv + kvh) * (kD * 2);
-    auto load_tile = [&](int kt, int buf) {
+    auto load_tile = [&](int kt, int t) { // t: tile number inside the work item
+        const int kbuf = t & 3, vbuf = t % kNumBufsV;
         if (kt < np_tiles && (kt + 1) * kBN <= P) {
             gptr kp[2], vp[2];
 #pragma unroll
@@ -303,14 +309,14 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
                 kp[i] = base + pg_lane_k;
                 vp[i] = base + pg_lane_v;
             }
-            dma_tile(kp[0], vp[0], kp[1], vp[1], buf);
+            dma_tile(kp[0], vp[0], kp[1], vp[1], kbuf, vbuf);
             return;
         }
         if (kt >= np_tiles && (kt - np_tiles + 1) * kBN <= E) {
             const int64_t tile_off = (int64_t)(kt - np_tiles) * kBN * row_bytes;
             const int64_t off1 = tile_off + (int64_t)kLoadRows * row_bytes;
             dma_tile(knew_head + tile_off + sfx_lane_k, vnew_head + tile_off + sfx_lane_v,
-                     knew_head + off1 + sfx_lane_k, vnew_head + off1 + sfx_lane_v, buf);
+                     knew_head + off1 + sfx_lane_k, vnew_head + off1 + sfx_lane_v, kbuf, vbuf);
             return;
         }
         const uint16_t *ks[2];
@@ -336,7 +342,7 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
                 vs[i] = p.v_new + base + off + cv * 8;
             }
         }
-        dma_tile((gptr)ks[0], (gptr)vs[0], (gptr)ks[1], (gptr)vs[1], buf);
+        dma_tile((gptr)ks[0], (gptr)vs[0], (gptr)ks[1], (gptr)vs[1], kbuf, vbuf);
     };
 
     // ---- per-lane LDS read offsets (bytes inside a tile buffer)
@@ -468,11 +474,11 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
             for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
     };
 
-    // ---- main loop, one barrier per key tile.  Iteration `it`:
-    //     request tile it+2: global memory -> LDS buffer (it+2) % 4, asynchronously
+    // ---- main loop, one barrier per two key tiles.  Iteration `it`:
+    //     request tile it+2: global memory -> K buffer (it+2) % 4, V buffer (it+2) % 5, asynchronously
     //     S = K(it) Q^T                                            (MFMA)
     //     p = exp2(S - m_ref) next to O += V(it-1)^T P(it-1)^T     (VALU next to MFMA)
-    //     wait for the requested tile, barrier
+    //     if `it` is even: wait for the requested tiles, barrier
     // (S already carries softmax_scale * log2(e), see the Q fragments.)  The exponentials are
     // taken against the running reference m_ref WITHOUT first reducing the row maximum of the
     // tile.  Only when some row of the wavefront has no reference yet, or its sum shows that the
@@ -532,23 +538,30 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
         dma_wait();
         __syncthreads();
     }
+    // The barrier comes after every second tile (after the even ones): a function of the tile
+    // number alone, so every wavefront meets the same barriers whichever loop it is in.
+    auto pair_barrier = [&](int it) {
+        if (!(it & 1)) {
+            dma_wait();
+            __syncthreads();
+        }
+    };
     // One full step; only called for tiles this wavefront does not skip (so the previous tile
     // was not skipped either and its probabilities are pending).
     auto tile_step = [&](int it, PTile &pb_cur, PTile &pb_prev) {
         const int buf = it & 3;
         const int kt = kt_begin + it;
         const bool prefetch = it + 2 < n_it;
-        if (prefetch) load_tile(kt + 2, (buf + 2) & 3);
+        if (prefetch) load_tile(kt + 2, it + 2);
         STile s;
         masked_qk(kt, buf, s);
         // one basic block: the exponentials (VALU) interleave with P V (MFMA)
         float psum = exp_tile(s, pb_cur, (m_ref == -INFINITY) ? 0.f : m_ref, std::false_type{});
-        pv_tile((buf + 3) & 3, pb_prev);
+        pv_tile((it - 1) % kNumBufsV, pb_prev);
         if (__builtin_amdgcn_ballot_w64(!(psum < kStale) || m_ref == -INFINITY) != 0)
             psum = redo_tile(s, pb_cur);
         l_run += psum;
-        dma_wait();
-        __syncthreads();
+        pair_barrier(it);
     };
     int it = 1;
     if (have_prev) {
@@ -573,6 +586,8 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
                 return (uint32_t)table[min(kt * (kBN / kPS) + 2 * i + tsel, last_entry)];
             };
             uint32_t pg0 = entry(kt_begin + it + 2, 0), pg1 = entry(kt_begin + it + 2, 1);
+            int vprev = (it - 1) % kNumBufsV; // V buffer of tile it - 1
+            auto vnext = [](int v, int n) { v += n; return v >= kNumBufsV ? v - kNumBufsV : v; };
             // while every row of the wavefront has the reference 0 (the usual case, see kSnap);
             // otherwise the general step below takes over
             for (; it < fast_end && __builtin_amdgcn_ballot_w64(m_ref != 0.f) == 0; ++it) {
@@ -593,18 +608,18 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
                     k1 = k0 + (int64_t)kLoadRows * row_bytes;
                     v1 = v0 + (int64_t)kLoadRows * row_bytes;
                 }
-                dma_tile(k0, v0, k1, v1, (buf + 2) & 3);
+                dma_tile(k0, v0, k1, v1, (buf + 2) & 3, vnext(vprev, 3));
                 pg0 = entry(kt_begin + it + 3, 0);
                 pg1 = entry(kt_begin + it + 3, 1);
                 STile s;
                 qk_tile(buf, s);
                 float psum = exp_tile(s, pb_b, 0.f, std::true_type{});
-                pv_tile((buf + 3) & 3, pb_a);
+                pv_tile(vprev, pb_a);
                 if (__builtin_amdgcn_ballot_w64(!(psum < kStale) || m_ref == -INFINITY) != 0)
                     psum = redo_tile(s, pb_b);
                 l_run += psum;
-                dma_wait();
-                __syncthreads();
+                pair_barrier(it);
+                vprev = vnext(vprev, 1);
 #pragma unroll
                 for (int t = 0; t < 2 * kNKB; ++t) pb_a[t] = pb_b[t];
             }
@@ -616,16 +631,15 @@ __global__ __launch_bounds__(kThreads) void extend_attn_kernel(const AttnParams 
             for (int t = 0; t < 2 * kNKB; ++t) pb_a[t] = pb_b[t];
         }
         // P V of the last tile this wavefront computed (tile it - 1)
-        pv_tile((it - 1) & 3, pb_a);
+        pv_tile((it - 1) % kNumBufsV, pb_a);
     }
     // remaining tiles are invisible to this wavefront: only take part in the cooperative loads
     for (; it < n_it; ++it) {
         const bool prefetch = it + 2 < n_it;
         if (prefetch) {
-            load_tile(kt_begin + it + 2, (it + 2) & 3);
+            load_tile(kt_begin + it + 2, it + 2);
         }
-        dma_wait();
-        __syncthreads();
+        pair_barrier(it);
     }
 
     // ---- epilogue.  o[db][v] is O^T[d = db*32 + 8*(v/4) + 4*h + v%4][row j]
