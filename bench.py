@@ -30,9 +30,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # valid only for the kernel source they were taken with: reported as null as soon as that source
 # changes.  They are not measured by this script.
 TRAFFIC = {
-    "source_sha256_16": "3b7865a3aeaa212c",
+    "source_sha256_16": "a2c80300eae4aaf4",
     "from": "profiles/extend_attn_kernel_long_context_32k.md, profiles/decode_attn_kernel_decode_b32_p10k.md",
-    "long_context_32k": (2130360 * 2.0 + 524289) * 1024.0,      # extend_attn_kernel
+    "long_context_32k": (2130379 * 2.0 + 524296) * 1024.0,      # extend_attn_kernel
     "decode_b32_p10k": (656155 * 2.0 + 4160) * 1024.0,          # decode_attn_kernel
 }
 
