@@ -262,6 +262,17 @@ def test_leftover_lds_contents_do_not_reach_the_result(H, case):
     _check(outs[0], oracle.attention_of(w), f"lds leftovers {case}")
 
 
+@pytest.mark.parametrize("tiles", range(1, 10))
+def test_every_small_tile_count(H, tiles):
+    """1 to 9 key tiles of 64 per work item, through the row-tiled kernel (num_splits = 1): the
+    loop requests tiles two ahead and meets at a barrier after every second tile, so the first
+    tiles, an odd and an even last tile and the cases without any prefetch are all here."""
+    n = 64 * tiles
+    for P, E in ((0, n - 10), (n - 7, 5), (n - 64, 64), (max(n - 100, 0), min(n, 100))):
+        w = W.make_uniform(f"tiles{tiles}_{P}_{E}", 150 + tiles, 2, 4, 2, [P, max(P - 3, 0)], [E, E])
+        _check(H.gpu_attention(w, num_splits=1), oracle.attention_of(w), f"tiles={tiles} P={P} E={E}")
+
+
 def test_error_paths_return_codes(H):
     import paper_2511_03475_amd as cp
     w = W.make_uniform("err", 110, 1, 4, 2, 32, 32)
